@@ -1,0 +1,211 @@
+/* sida_moe.h — C ABI of the SiDA-MoE layer hot path for AMD MI355X (gfx950).
+ *
+ * The library serves one sparse Mixture-of-Experts layer at a time the way the paper's inference
+ * thread does (Section 3.1; Algorithm 1, left column): the expert id and the scaling factor
+ * alpha of every token come from a table that was built ahead of time (the "hash table" H[l][s]),
+ * routers take no part, only experts that have tokens are invoked (Section 2.2), and only the
+ * experts a batch activates are kept in GPU memory, in a pool of S equal-sized slots that is
+ * filled from host memory and replaced first-in-first-out (Section 3.1, Section 4.3).
+ *
+ * Layer output (Section 2.1, Eq. 1 with the Switch top-1 selection):
+ *     y[t,:] = alpha[t] * W_out[k] * relu(W_in[k] * x[t,:]),     k = expert_ids[t]
+ *
+ * Conventions
+ *  - "host" pointers are ordinary process memory; "device" pointers are HIP device memory of the
+ *    current device.  The library never allocates or frees device memory: x, y, ids, alpha, the
+ *    slot pool and the workspace are the caller's, and so are the pinned host weight blocks.
+ *  - Streams are passed as raw hipStream_t values cast to void* (NULL = the null stream).
+ *  - bf16 = bfloat16 (upper half of an IEEE fp32).  All matrices are row-major.
+ *  - One expert is ONE contiguous block of sida_expert_bytes() bytes:
+ *        W_in  bf16 [d_ff, d_model]   (row j = weights of hidden unit j), immediately followed by
+ *        W_out bf16 [d_model, d_ff].
+ *    Slot s of the pool is the byte range [s*expert_bytes, (s+1)*expert_bytes).
+ *  - Every function returns SIDA_OK (0) or a negative sida_status.  On an error nothing has been
+ *    enqueued and no bookkeeping has changed.  Faults of work that was already enqueued show up
+ *    at the caller's next stream synchronisation, as with any HIP work.
+ *  - A context is not thread-safe; use one per serving thread.  All compute of one context must
+ *    be enqueued on one stream, all copies on one (other) stream.
+ *  - Limits: 1 <= E <= SIDA_MAX_E; d_model and d_ff multiples of 128; 1 <= W <= S.
+ */
+#ifndef SIDA_MOE_H
+#define SIDA_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SIDA_MAX_E 256
+
+typedef enum sida_status {
+    SIDA_OK = 0,
+    SIDA_EINVAL = -1,   /* null pointer, bad shape, expert id outside [0,E), bad wave index   */
+    SIDA_ENOSPC = -2,   /* workspace or pool smaller than required                            */
+    SIDA_ESTATE = -3,   /* pool / host weights not bound, stale plan, calls out of wave order  */
+    SIDA_EHIP = -4,     /* a HIP call failed; see sida_last_hip_error()                        */
+    SIDA_ENOMEM = -5    /* host allocation failed                                              */
+} sida_status;
+
+typedef struct sida_ctx sida_ctx; /* opaque: host bookkeeping and HIP events only */
+
+typedef struct sida_config {
+    int32_t L;        /* MoE layers sharing the pool                                         */
+    int32_t E;        /* experts per layer                                                   */
+    int32_t d_model;  /* token width d                                                       */
+    int32_t d_ff;     /* hidden width F of an expert                                         */
+    int32_t S;        /* expert slots in the pool (the GPU memory budget of Section 3.1)     */
+    int32_t W;        /* most experts computed together as one wave, 1..S                    */
+    int32_t max_T;    /* most tokens per layer call                                          */
+} sida_config;
+
+/* Residency plan of one layer for one batch: the outcome of Algorithm 1's loop "for each token:
+ * check its expert; if it is not on the GPU, move it there" under the FIFO budget.  Plain data,
+ * owned by the caller, filled by sida_moe_plan().  Arrays indexed by expert id hold -1 for
+ * experts without tokens (they are never loaded nor invoked).  Waves carry a global index that
+ * counts up over the life of the pool; a layer's waves are first_wave .. first_wave+n_waves-1. */
+typedef struct sida_plan {
+    int32_t layer, T, E;
+    int32_t n_active;                      /* experts with at least one token                        */
+    int32_t n_waves;                       /* 0 iff T == 0                                           */
+    int32_t first_wave;                    /* global index of the layer's first wave, -1 if none     */
+    uint32_t epoch;                        /* pool generation the plan belongs to (see pool_reset)   */
+    int32_t n_miss;                        /* experts that have to be copied host -> pool            */
+    int32_t counts[SIDA_MAX_E];            /* tokens per expert                                      */
+    int32_t offsets[SIDA_MAX_E + 1];       /* exclusive prefix sum of counts; offsets[E] == T        */
+    int32_t order[SIDA_MAX_E];             /* activated experts in order of first appearance         */
+    int32_t slot[SIDA_MAX_E];              /* pool slot holding the expert while its wave computes   */
+    int32_t wave[SIDA_MAX_E];              /* global wave the expert is computed in                  */
+    int32_t hit[SIDA_MAX_E];               /* 1: already resident, 0: must be copied                 */
+    int32_t evicted_key[SIDA_MAX_E];       /* layer*E+e overwritten by this expert's copy, -1 none   */
+    int32_t wave_dep[SIDA_MAX_E];          /* per local wave: global wave whose compute must finish
+                                              before this wave's copies may start, -1 if none       */
+} sida_plan;
+
+/* Byte offsets of the regions inside the caller's workspace for a call with T tokens (tests and
+ * profilers read intermediates through these). */
+typedef struct sida_ws_layout {
+    size_t counts;      /* int32 [E]                    tokens per expert                     */
+    size_t offsets;     /* int32 [E+1]                  exclusive prefix sum                  */
+    size_t block_hist;  /* int32 [n_blocks*E]           per-block histograms, then bases      */
+    size_t perm;        /* int32 [T]   perm[r] = t      stable order by (expert, token)       */
+    size_t inv;         /* int32 [T]   inv[t]  = r                                            */
+    size_t x_perm;      /* bf16  [T, d_model]           x rows in perm order                  */
+    size_t h;           /* bf16  [T, d_ff]              relu(x_perm W_in^T), perm order       */
+    size_t y_perm;      /* bf16  [T, d_model]           expert outputs, perm order            */
+    size_t total;       /* bytes needed                                                       */
+} sida_ws_layout;
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Validates cfg and creates a context with an empty pool.  Touches no GPU. */
+int sida_create(const sida_config *cfg, sida_ctx **out);
+/* Destroys the context and its HIP events.  Does not synchronise: the caller must have drained
+ * the streams first.  NULL is allowed. */
+void sida_destroy(sida_ctx *ctx);
+const char *sida_strerror(int code);
+/* hipError_t (as int) of the HIP call behind the last SIDA_EHIP of this context, else 0. */
+int sida_last_hip_error(const sida_ctx *ctx);
+
+/* 4 * d_model * d_ff: W_in and W_out of one expert in bf16 (two d_model x d_ff matrices, the
+ * per-expert parameter count behind Table 2 of Section 2.2). */
+size_t sida_expert_bytes(const sida_ctx *ctx);
+/* Workspace bytes a layer call with T tokens needs (0 on bad arguments). */
+size_t sida_workspace_bytes(const sida_ctx *ctx, int32_t T);
+int sida_workspace_layout(const sida_ctx *ctx, int32_t T, sida_ws_layout *out);
+
+/* pool_dev: device memory, 256-byte aligned, bytes >= S * expert_bytes, owned by the caller and
+ * kept alive while the context uses it. */
+int sida_bind_pool(sida_ctx *ctx, void *pool_dev, size_t bytes);
+/* host_blocks: host array of L*E pointers, entry layer*E+e -> that expert's block in PINNED host
+ * memory (pageable memory works but makes the copies synchronous).  The pointer table is copied;
+ * the blocks stay the caller's and must outlive every prefetch that reads them. */
+int sida_bind_host_weights(sida_ctx *ctx, const void *const *host_blocks);
+/* Forgets every resident expert: empty pool, FIFO cursor 0, wave counter 0, new epoch (plans
+ * made before the reset are stale).  The caller must have drained both streams. */
+int sida_pool_reset(sida_ctx *ctx);
+/* Inspection: slot_key[S] (layer*E+e or -1 per slot), FIFO cursor, next global wave index.  Any
+ * output pointer may be NULL. */
+int sida_pool_state(const sida_ctx *ctx, int32_t *slot_key, int32_t *cursor, int32_t *next_wave);
+
+/* ---- the three calls of the method --------------------------------------------------------- */
+
+/* moe_plan(expert_ids) -> residency plan.  Algorithm 1, inference thread: walks the tokens of
+ * `layer` in order, checks each token's expert against the pool and schedules a load for every
+ * expert that is not resident; slots are reused first-in-first-out (Section 3.1), a hit does not
+ * renew an expert's age, and the budget is shared by all layers.  When a layer activates more
+ * experts than one wave may hold, it is cut into waves of at most W experts.
+ * Host only, integers only, synchronous.  Updates the pool BOOKKEEPING (which key each slot will
+ * hold once the plan's copies ran); plans must be made in the order their layers will run.
+ * ids_host: host int32 [T], 0 <= T <= max_T.  An id outside [0,E) -> SIDA_EINVAL, state unchanged. */
+int sida_moe_plan(sida_ctx *ctx, int32_t layer, const int32_t *ids_host, int32_t T, sida_plan *out);
+
+/* expert_prefetch(slot_table, host_weights, stream): enqueues, on copy_stream, the host -> pool
+ * copies of the experts that local wave `wave` of `plan` misses (one copy of expert_bytes each),
+ * after making copy_stream wait for the compute of wave_dep[wave] — the last wave that read a
+ * slot about to be overwritten.  This is the "load the activated experts ahead of the forward
+ * pass, overlapped with the previous compute" step of Section 3.1.
+ * Waves must be prefetched in global order; a wave that was already prefetched is a no-op (0).
+ * SIDA_ESTATE if an earlier wave has not been prefetched yet, or if the forward call of
+ * wave_dep[wave] has not been enqueued yet (the wait could not be expressed). */
+int sida_expert_prefetch(sida_ctx *ctx, const sida_plan *plan, int32_t wave, void *copy_stream);
+
+/* moe_layer_forward(x, expert_ids, gate_w, slot_table) -> y.  Eq. 1 of Section 2.1 for the T
+ * tokens of plan->layer, evaluated as: stable counting sort of the tokens by expert id and
+ * gather of their rows; per wave, wait for its copies, then the grouped expert FFN
+ * (W_in GEMM, ReLU, W_out GEMM on bf16 MFMA, fp32 accumulate, experts addressed through the
+ * plan's slot table); gate-weighted scatter back to token order.
+ *   x_dev     bf16 [T, d_model]    device, read
+ *   ids_dev   int32 [T]            device, read; must equal the ids the plan was made from
+ *   alpha_dev fp32 [T]             device, read; the per-token scaling factor (gate value)
+ *   y_dev     bf16 [T, d_model]    device, written
+ *   workspace_dev                  device, >= sida_workspace_bytes(T), 256-byte aligned, scratch
+ * Everything is enqueued on compute_stream; waves that were not prefetched yet are prefetched by
+ * this call on copy_stream (one wave ahead of the compute where wave_dep allows).  Layers must
+ * be forwarded in the order they were planned.  Asynchronous. */
+int sida_moe_layer_forward(sida_ctx *ctx, const sida_plan *plan, const void *x_dev,
+                           const int32_t *ids_dev, const float *alpha_dev, void *y_dev,
+                           void *workspace_dev, size_t workspace_bytes, void *compute_stream,
+                           void *copy_stream);
+
+/* Convenience: forwards n consecutive planned layers, keeping the copy stream one wave ahead of
+ * the compute across layer boundaries too (the first wave of layer i+1 is copied while the last
+ * wave of layer i computes).  plans[i], x_dev[i], ids_dev[i], alpha_dev[i], y_dev[i] belong to
+ * the i-th layer of the call; arrays of pointers live in host memory. */
+int sida_run_layers(sida_ctx *ctx, int32_t n, const sida_plan *const *plans,
+                    const void *const *x_dev, const int32_t *const *ids_dev,
+                    const float *const *alpha_dev, void *const *y_dev, void *workspace_dev,
+                    size_t workspace_bytes, void *compute_stream, void *copy_stream);
+
+/* ---- single stages (the pieces moe_layer_forward is made of; for tests and profiling) ------- */
+
+/* Counting sort + permute-gather only: fills counts, offsets, perm, inv and x_perm of the
+ * workspace for ids_dev / x_dev.  E and d_model come from the context. */
+int sida_dispatch(sida_ctx *ctx, const void *x_dev, const int32_t *ids_dev, int32_t T,
+                  void *workspace_dev, size_t workspace_bytes, void *stream);
+/* Grouped FFN of one local wave of `plan`: reads x_perm and offsets from the workspace (as left
+ * by sida_dispatch on the same ids), the experts from their pool slots; writes h and y_perm rows
+ * of the wave's experts.  No stream waits, no bookkeeping: the caller guarantees residency. */
+int sida_grouped_ffn(sida_ctx *ctx, const sida_plan *plan, int32_t wave, void *workspace_dev,
+                     size_t workspace_bytes, void *stream);
+/* Gate-weighted scatter-combine only: y[t,:] = alpha[t] * y_perm[inv[t],:]. */
+int sida_combine(sida_ctx *ctx, const float *alpha_dev, int32_t T, void *y_dev,
+                 void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ---- kernel timing (for the benchmark's roofline figures) ----------------------------------- */
+
+enum { SIDA_K_SORT = 0, SIDA_K_GATHER = 1, SIDA_K_GEMM1 = 2, SIDA_K_GEMM2 = 3, SIDA_K_COMBINE = 4,
+       SIDA_K_COPY = 5, SIDA_K_COUNT = 6 };
+/* When enabled, every launch (and every wave's batch of copies) is bracketed by timing events on
+ * the stream it is enqueued on.  Costs two event records per launch.  Off by default. */
+int sida_profile_enable(sida_ctx *ctx, int32_t on);
+/* Synchronises the recorded events, adds their durations to the per-class totals and returns the
+ * totals since the last reset: ms[SIDA_K_COUNT], launches[SIDA_K_COUNT].  The caller must have
+ * synchronised the streams. */
+int sida_profile_read(sida_ctx *ctx, double *ms, int64_t *launches, int32_t reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIDA_MOE_H */

@@ -1,0 +1,538 @@
+// Host side of the C ABI: context, pool binding, expert prefetch, layer forward.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "ctx.h"
+#include "kernels.h"
+
+using namespace sida;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define HIP_TRY(ctx, expr)                           \
+    do {                                             \
+        hipError_t err__ = (expr);                   \
+        if (err__ != hipSuccess) {                   \
+            (ctx)->last_hip = (int)err__;            \
+            return SIDA_EHIP;                        \
+        }                                            \
+    } while (0)
+
+int make_events(sida_ctx *c)
+{
+    if (c->events_made) return SIDA_OK;
+    c->ev_ready.assign(kEventRing, nullptr);
+    c->ev_done.assign(kEventRing, nullptr);
+    c->ready_recorded.assign(kEventRing, 0);
+    for (int i = 0; i < kEventRing; ++i) {
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming));
+    }
+    c->events_made = true;
+    return SIDA_OK;
+}
+
+void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
+{
+    const size_t n_chunks = ((size_t)T + kSortChunk - 1) / kSortChunk;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    o->counts = take(sizeof(int32_t) * (size_t)cfg.E);
+    o->offsets = take(sizeof(int32_t) * ((size_t)cfg.E + 1));
+    o->block_hist = take(sizeof(int32_t) * std::max<size_t>(1, n_chunks) * (size_t)cfg.E);
+    o->perm = take(sizeof(int32_t) * (size_t)T);
+    o->inv = take(sizeof(int32_t) * (size_t)T);
+    o->x_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
+    o->h = take(2 * (size_t)T * (size_t)cfg.d_ff);
+    o->y_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
+    o->total = off;
+}
+
+struct Ws {
+    int32_t *counts, *offsets, *block_hist, *perm, *inv;
+    void *x_perm, *h, *y_perm;
+};
+
+Ws carve(const sida_config &cfg, int32_t T, void *base)
+{
+    sida_ws_layout l;
+    layout(cfg, T, &l);
+    char *b = static_cast<char *>(base);
+    return Ws{(int32_t *)(b + l.counts), (int32_t *)(b + l.offsets), (int32_t *)(b + l.block_hist),
+              (int32_t *)(b + l.perm),   (int32_t *)(b + l.inv),     b + l.x_perm,
+              b + l.h,                   b + l.y_perm};
+}
+
+int check_plan(const sida_ctx *c, const sida_plan *p)
+{
+    if (!c || !p) return SIDA_EINVAL;
+    if (p->epoch != c->epoch) return SIDA_ESTATE;
+    if (p->E != c->cfg.E || p->layer < 0 || p->layer >= c->cfg.L || p->T < 0 || p->T > c->cfg.max_T) return SIDA_EINVAL;
+    if (p->n_waves < 0 || p->n_active < 0 || p->n_active > c->cfg.E) return SIDA_EINVAL;
+    if (p->n_waves > 0 && (p->first_wave < 0 || p->first_wave + p->n_waves > c->next_wave)) return SIDA_ESTATE;
+    return SIDA_OK;
+}
+
+int check_ws(const sida_ctx *c, int32_t T, const void *ws, size_t bytes)
+{
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SIDA_EINVAL;
+    sida_ws_layout l;
+    layout(c->cfg, T, &l);
+    return bytes < l.total ? SIDA_ENOSPC : SIDA_OK;
+}
+
+// ---- kernel timing -------------------------------------------------------------------------
+struct Timed {
+    sida_ctx *c;
+    hipStream_t st;
+    ProfRec *rec = nullptr;
+    Timed(sida_ctx *ctx, int klass, hipStream_t s) : c(ctx), st(s)
+    {
+        if (!c->profiling) return;
+        if (c->prof_used == c->prof_pool.size()) {
+            if (c->prof_pool.size() >= (size_t)kProfRing) return;     // ring full: launch goes untimed
+            ProfRec r{};
+            if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+            c->prof_pool.push_back(r);
+        }
+        rec = &c->prof_pool[c->prof_used++];
+        rec->klass = klass;
+        (void)hipEventRecord(rec->start, st);
+    }
+    ~Timed()
+    {
+        if (rec) (void)hipEventRecord(rec->stop, st);
+    }
+};
+
+// The wave table of local wave w: the wave's experts, most tokens first (their tiles are
+// scheduled first so the long experts do not end up as the tail of the launch).
+void build_wave_table(const sida_plan *p, int32_t w, WaveTable *t)
+{
+    const int32_t g = p->first_wave + w;
+    int32_t idx[SIDA_MAX_E];
+    int32_t n = 0;
+    for (int32_t i = 0; i < p->n_active; ++i) {
+        const int32_t e = p->order[i];
+        if (p->wave[e] == g) idx[n++] = e;
+    }
+    std::stable_sort(idx, idx + n, [&](int32_t a, int32_t b) { return p->counts[a] > p->counts[b]; });
+    t->n = n;
+    t->m_tiles = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        t->expert[i] = (uint8_t)idx[i];
+        t->slot[i] = (int16_t)p->slot[idx[i]];
+        t->m_tiles += (p->counts[idx[i]] + kGemmTileM - 1) / kGemmTileM;
+    }
+}
+
+// Copies of local wave w (global g).  Caller has checked order and dependencies.
+int enqueue_prefetch(sida_ctx *c, const sida_plan *p, int32_t w, hipStream_t copy)
+{
+    const int32_t g = p->first_wave + w;
+    const int ring = g % kEventRing;
+    int32_t misses = 0;
+    for (int32_t i = 0; i < p->n_active; ++i) {
+        const int32_t e = p->order[i];
+        if (p->wave[e] == g && p->hit[e] == 0) ++misses;
+    }
+    c->ready_recorded[ring] = 0;
+    if (misses) {
+        if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_ready[ring]));   // slot of wave g - ring
+        const int32_t dep = p->wave_dep[w];
+        if (dep >= 0) HIP_TRY(c, hipStreamWaitEvent(copy, c->ev_done[dep % kEventRing], 0));
+        {
+            Timed tm(c, SIDA_K_COPY, copy);
+            for (int32_t i = 0; i < p->n_active; ++i) {
+                const int32_t e = p->order[i];
+                if (p->wave[e] != g || p->hit[e] != 0) continue;
+                const void *src = c->host_blocks[(size_t)p->layer * c->cfg.E + e];
+                HIP_TRY(c, hipMemcpyAsync(c->pool + (size_t)p->slot[e] * c->expert_bytes, src, c->expert_bytes,
+                                          hipMemcpyHostToDevice, copy));
+            }
+        }
+        HIP_TRY(c, hipEventRecord(c->ev_ready[ring], copy));
+        c->ready_recorded[ring] = 1;
+    }
+    c->prefetched_upto = g + 1;
+    return SIDA_OK;
+}
+
+int prefetch_allowed(const sida_ctx *c, const sida_plan *p, int32_t w)
+{
+    const int32_t g = p->first_wave + w;
+    if (g != c->prefetched_upto) return SIDA_ESTATE;
+    if (p->wave_dep[w] >= c->forwarded_upto) return SIDA_ESTATE;
+    return SIDA_OK;
+}
+
+int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, const Ws &ws, hipStream_t st)
+{
+    {
+        Timed tm(c, SIDA_K_SORT, st);
+        HIP_TRY(c, (hipError_t)launch_sort(ids, T, c->cfg.E, ws.counts, ws.offsets, ws.block_hist, ws.perm, ws.inv, st));
+    }
+    {
+        Timed tm(c, SIDA_K_GATHER, st);
+        HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st));
+    }
+    return SIDA_OK;
+}
+
+int launch_wave_ffn(sida_ctx *c, const sida_plan *p, int32_t w, const Ws &ws, hipStream_t st)
+{
+    WaveTable tbl;
+    build_wave_table(p, w, &tbl);
+    {
+        Timed tm(c, SIDA_K_GEMM1, st);
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, ws.offsets, tbl,
+                                                c->cfg.d_model, c->cfg.d_ff, st));
+    }
+    {
+        Timed tm(c, SIDA_K_GEMM2, st);
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, ws.offsets, tbl,
+                                                c->cfg.d_model, c->cfg.d_ff, st));
+    }
+    return SIDA_OK;
+}
+
+struct LayerArgs {
+    const sida_plan *plan;
+    const void *x;
+    const int32_t *ids;
+    const float *alpha;
+    void *y;
+};
+
+int check_layer_args(const sida_ctx *c, const LayerArgs &a)
+{
+    int rc = check_plan(c, a.plan);
+    if (rc) return rc;
+    if (a.plan->T > 0 && (!a.x || !a.ids || !a.alpha || !a.y)) return SIDA_EINVAL;
+    return SIDA_OK;
+}
+
+// Forwards `n` consecutive layers.  The copy stream is kept one wave ahead of the compute
+// whenever the next wave's dependency has already been enqueued.
+int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev, size_t ws_bytes,
+                   hipStream_t compute, hipStream_t copy)
+{
+    if (!c->pool || c->host_blocks.empty()) return SIDA_ESTATE;
+    int32_t expect = c->forwarded_upto;
+    for (int32_t i = 0; i < n; ++i) {
+        int rc = check_layer_args(c, layers[i]);
+        if (rc) return rc;
+        const sida_plan *p = layers[i].plan;
+        if (p->n_waves == 0) continue;
+        if (p->first_wave != expect) return SIDA_ESTATE;           // layers out of planned order
+        expect += p->n_waves;
+        rc = check_ws(c, p->T, ws_dev, ws_bytes);
+        if (rc) return rc;
+    }
+    int rc = make_events(c);
+    if (rc) return rc;
+
+    // flat list of (layer, local wave) still to forward, to find "the next wave" across layers
+    auto next_of = [&](int32_t li, int32_t w, int32_t *nli, int32_t *nw) {
+        ++w;
+        while (li < n && w >= layers[li].plan->n_waves) {
+            ++li;
+            w = 0;
+        }
+        *nli = li;
+        *nw = w;
+        return li < n;
+    };
+    auto try_prefetch = [&](int32_t li, int32_t w) -> int {
+        const sida_plan *p = layers[li].plan;
+        const int32_t g = p->first_wave + w;
+        if (g < c->prefetched_upto) return SIDA_OK;                // done earlier (by the caller)
+        if (prefetch_allowed(c, p, w) != SIDA_OK) return 1;        // not yet possible
+        return enqueue_prefetch(c, p, w, copy);
+    };
+
+    for (int32_t li = 0; li < n; ++li) {
+        const LayerArgs &a = layers[li];
+        const sida_plan *p = a.plan;
+        if (p->n_waves == 0) continue;
+        const Ws ws = carve(c->cfg, p->T, ws_dev);
+        rc = launch_dispatch(c, a.x, a.ids, p->T, ws, compute);
+        if (rc) return rc;
+        for (int32_t w = 0; w < p->n_waves; ++w) {
+            const int32_t g = p->first_wave + w;
+            rc = try_prefetch(li, w);
+            if (rc < 0) return rc;
+            if (rc > 0) return SIDA_ESTATE;                        // cannot happen: wave_dep < g
+            int32_t nli, nw;
+            if (next_of(li, w, &nli, &nw)) {
+                rc = try_prefetch(nli, nw);                        // look one wave ahead
+                if (rc < 0) return rc;
+            }
+            const int ring = g % kEventRing;
+            if (c->ready_recorded[ring]) HIP_TRY(c, hipStreamWaitEvent(compute, c->ev_ready[ring], 0));
+            rc = launch_wave_ffn(c, p, w, ws, compute);
+            if (rc) return rc;
+            if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_done[ring]));
+            HIP_TRY(c, hipEventRecord(c->ev_done[ring], compute));
+            c->forwarded_upto = g + 1;
+        }
+        {
+            Timed tm(c, SIDA_K_COMBINE, compute);
+            HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute));
+        }
+    }
+    return SIDA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sida_create(const sida_config *cfg, sida_ctx **out)
+{
+    if (!cfg || !out) return SIDA_EINVAL;
+    *out = nullptr;
+    if (cfg->L < 1 || cfg->E < 1 || cfg->E > SIDA_MAX_E || cfg->S < 1 || cfg->S > 32767 || cfg->W < 1 ||
+        cfg->W > cfg->S || cfg->W > SIDA_MAX_E || cfg->max_T < 0 || cfg->d_model < 128 || cfg->d_ff < 128 ||
+        cfg->d_model % 128 || cfg->d_ff % 128)
+        return SIDA_EINVAL;
+    if ((int64_t)cfg->L * cfg->E > INT32_MAX) return SIDA_EINVAL;
+    sida_ctx *c = new (std::nothrow) sida_ctx;
+    if (!c) return SIDA_ENOMEM;
+    try {
+        c->cfg = *cfg;
+        c->expert_bytes = (size_t)4 * cfg->d_model * cfg->d_ff;
+        c->slot_key.assign(cfg->S, -1);
+        c->last_use.assign(cfg->S, -1);
+        c->key_slot.assign((size_t)cfg->L * cfg->E, -1);
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return SIDA_ENOMEM;
+    }
+    *out = c;
+    return SIDA_OK;
+}
+
+void sida_destroy(sida_ctx *c)
+{
+    if (!c) return;
+    if (c->events_made)
+        for (int i = 0; i < kEventRing; ++i) {
+            if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
+            if (c->ev_done[i]) (void)hipEventDestroy(c->ev_done[i]);
+        }
+    for (auto &r : c->prof_pool) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    delete c;
+}
+
+const char *sida_strerror(int code)
+{
+    switch (code) {
+        case SIDA_OK: return "ok";
+        case SIDA_EINVAL: return "invalid argument";
+        case SIDA_ENOSPC: return "workspace or pool too small";
+        case SIDA_ESTATE: return "call not valid in this state (unbound pool/weights, stale plan or wrong order)";
+        case SIDA_EHIP: return "HIP call failed";
+        case SIDA_ENOMEM: return "out of host memory";
+        default: return "unknown status";
+    }
+}
+
+int sida_last_hip_error(const sida_ctx *c) { return c ? c->last_hip : 0; }
+
+size_t sida_expert_bytes(const sida_ctx *c) { return c ? c->expert_bytes : 0; }
+
+size_t sida_workspace_bytes(const sida_ctx *c, int32_t T)
+{
+    if (!c || T < 0 || T > c->cfg.max_T) return 0;
+    sida_ws_layout l;
+    layout(c->cfg, T, &l);
+    return l.total;
+}
+
+int sida_workspace_layout(const sida_ctx *c, int32_t T, sida_ws_layout *out)
+{
+    if (!c || !out || T < 0 || T > c->cfg.max_T) return SIDA_EINVAL;
+    layout(c->cfg, T, out);
+    return SIDA_OK;
+}
+
+int sida_bind_pool(sida_ctx *c, void *pool_dev, size_t bytes)
+{
+    if (!c || !pool_dev || (reinterpret_cast<uintptr_t>(pool_dev) & 255u)) return SIDA_EINVAL;
+    if (bytes < (size_t)c->cfg.S * c->expert_bytes) return SIDA_ENOSPC;
+    c->pool = static_cast<char *>(pool_dev);
+    c->pool_bytes = bytes;
+    return SIDA_OK;
+}
+
+int sida_bind_host_weights(sida_ctx *c, const void *const *host_blocks)
+{
+    if (!c || !host_blocks) return SIDA_EINVAL;
+    const size_t n = (size_t)c->cfg.L * c->cfg.E;
+    for (size_t i = 0; i < n; ++i)
+        if (!host_blocks[i]) return SIDA_EINVAL;
+    try {
+        c->host_blocks.assign(host_blocks, host_blocks + n);
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
+    return SIDA_OK;
+}
+
+int sida_pool_reset(sida_ctx *c)
+{
+    if (!c) return SIDA_EINVAL;
+    std::fill(c->slot_key.begin(), c->slot_key.end(), -1);
+    std::fill(c->last_use.begin(), c->last_use.end(), -1);
+    std::fill(c->key_slot.begin(), c->key_slot.end(), -1);
+    std::fill(c->ready_recorded.begin(), c->ready_recorded.end(), 0);
+    c->cursor = 0;
+    c->next_wave = 0;
+    c->prefetched_upto = 0;
+    c->forwarded_upto = 0;
+    ++c->epoch;
+    return SIDA_OK;
+}
+
+int sida_pool_state(const sida_ctx *c, int32_t *slot_key, int32_t *cursor, int32_t *next_wave)
+{
+    if (!c) return SIDA_EINVAL;
+    if (slot_key) std::memcpy(slot_key, c->slot_key.data(), sizeof(int32_t) * c->slot_key.size());
+    if (cursor) *cursor = c->cursor;
+    if (next_wave) *next_wave = c->next_wave;
+    return SIDA_OK;
+}
+
+int sida_moe_plan(sida_ctx *c, int32_t layer, const int32_t *ids_host, int32_t T, sida_plan *out)
+{
+    if (!c || !out || layer < 0 || layer >= c->cfg.L || T < 0 || T > c->cfg.max_T || (T > 0 && !ids_host))
+        return SIDA_EINVAL;
+    if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E) return SIDA_ESTATE;   // wave counter exhausted: reset the pool
+    return plan_layer(c, layer, ids_host, T, out);
+}
+
+int sida_expert_prefetch(sida_ctx *c, const sida_plan *plan, int32_t wave, void *copy_stream)
+{
+    int rc = check_plan(c, plan);
+    if (rc) return rc;
+    if (wave < 0 || wave >= plan->n_waves) return SIDA_EINVAL;
+    if (!c->pool || c->host_blocks.empty()) return SIDA_ESTATE;
+    if (plan->first_wave + wave < c->prefetched_upto) return SIDA_OK;
+    rc = prefetch_allowed(c, plan, wave);
+    if (rc) return rc;
+    rc = make_events(c);
+    if (rc) return rc;
+    return enqueue_prefetch(c, plan, wave, static_cast<hipStream_t>(copy_stream));
+}
+
+int sida_moe_layer_forward(sida_ctx *c, const sida_plan *plan, const void *x_dev, const int32_t *ids_dev,
+                           const float *alpha_dev, void *y_dev, void *workspace_dev, size_t workspace_bytes,
+                           void *compute_stream, void *copy_stream)
+{
+    if (!c || !plan) return SIDA_EINVAL;
+    LayerArgs a{plan, x_dev, ids_dev, alpha_dev, y_dev};
+    return forward_layers(c, 1, &a, workspace_dev, workspace_bytes, static_cast<hipStream_t>(compute_stream),
+                          static_cast<hipStream_t>(copy_stream));
+}
+
+int sida_run_layers(sida_ctx *c, int32_t n, const sida_plan *const *plans, const void *const *x_dev,
+                    const int32_t *const *ids_dev, const float *const *alpha_dev, void *const *y_dev,
+                    void *workspace_dev, size_t workspace_bytes, void *compute_stream, void *copy_stream)
+{
+    if (!c || n < 0 || (n > 0 && (!plans || !x_dev || !ids_dev || !alpha_dev || !y_dev))) return SIDA_EINVAL;
+    std::vector<LayerArgs> v;
+    try {
+        v.reserve(n);
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        if (!plans[i]) return SIDA_EINVAL;
+        v.push_back(LayerArgs{plans[i], x_dev[i], ids_dev[i], alpha_dev[i], y_dev[i]});
+    }
+    return forward_layers(c, n, v.data(), workspace_dev, workspace_bytes, static_cast<hipStream_t>(compute_stream),
+                          static_cast<hipStream_t>(copy_stream));
+}
+
+int sida_dispatch(sida_ctx *c, const void *x_dev, const int32_t *ids_dev, int32_t T, void *workspace_dev,
+                  size_t workspace_bytes, void *stream)
+{
+    if (!c || T < 0 || T > c->cfg.max_T) return SIDA_EINVAL;
+    if (T == 0) return SIDA_OK;
+    if (!x_dev || !ids_dev) return SIDA_EINVAL;
+    int rc = check_ws(c, T, workspace_dev, workspace_bytes);
+    if (rc) return rc;
+    return launch_dispatch(c, x_dev, ids_dev, T, carve(c->cfg, T, workspace_dev), static_cast<hipStream_t>(stream));
+}
+
+int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *workspace_dev, size_t workspace_bytes,
+                     void *stream)
+{
+    int rc = check_plan(c, plan);
+    if (rc) return rc;
+    if (wave < 0 || wave >= plan->n_waves) return SIDA_EINVAL;
+    if (!c->pool) return SIDA_ESTATE;
+    rc = check_ws(c, plan->T, workspace_dev, workspace_bytes);
+    if (rc) return rc;
+    return launch_wave_ffn(c, plan, wave, carve(c->cfg, plan->T, workspace_dev), static_cast<hipStream_t>(stream));
+}
+
+int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, void *workspace_dev,
+                 size_t workspace_bytes, void *stream)
+{
+    if (!c || T < 0 || T > c->cfg.max_T) return SIDA_EINVAL;
+    if (T == 0) return SIDA_OK;
+    if (!alpha_dev || !y_dev) return SIDA_EINVAL;
+    int rc = check_ws(c, T, workspace_dev, workspace_bytes);
+    if (rc) return rc;
+    const Ws ws = carve(c->cfg, T, workspace_dev);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Timed tm(c, SIDA_K_COMBINE, st);
+    HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st));
+    return SIDA_OK;
+}
+
+int sida_profile_enable(sida_ctx *c, int32_t on)
+{
+    if (!c) return SIDA_EINVAL;
+    c->profiling = on != 0;
+    return SIDA_OK;
+}
+
+int sida_profile_read(sida_ctx *c, double *ms, int64_t *launches, int32_t reset)
+{
+    if (!c) return SIDA_EINVAL;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        ProfRec &r = c->prof_pool[i];
+        HIP_TRY(c, hipEventSynchronize(r.stop));
+        float t = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&t, r.start, r.stop));
+        c->prof_ms[r.klass] += t;
+        c->prof_n[r.klass] += 1;
+    }
+    c->prof_used = 0;
+    for (int k = 0; k < SIDA_K_COUNT; ++k) {
+        if (ms) ms[k] = c->prof_ms[k];
+        if (launches) launches[k] = c->prof_n[k];
+        if (reset) {
+            c->prof_ms[k] = 0;
+            c->prof_n[k] = 0;
+        }
+    }
+    return SIDA_OK;
+}
+
+}  // extern "C"

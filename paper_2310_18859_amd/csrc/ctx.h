@@ -1,0 +1,63 @@
+// Internal definitions shared by the host-side sources of the library.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "sida_moe.h"
+
+namespace sida {
+
+constexpr int kEventRing = 512;        // waves whose events can be outstanding at once
+constexpr int kSortChunk = 256;        // tokens handled by one wavefront of the sort kernels
+constexpr int kProfRing = 8192;        // profiled launches between two sida_profile_read calls
+
+struct ProfRec {
+    hipEvent_t start, stop;
+    int klass;
+};
+
+}  // namespace sida
+
+struct sida_ctx {
+    sida_config cfg{};
+    size_t expert_bytes = 0;
+
+    // bound resources (caller-owned)
+    char *pool = nullptr;
+    size_t pool_bytes = 0;
+    std::vector<const void *> host_blocks;
+
+    // residency bookkeeping (Algorithm 1 + FIFO)
+    std::vector<int32_t> slot_key;     // [S] key held by each slot, -1 empty
+    std::vector<int32_t> key_slot;     // [L*E] slot holding the key, -1 absent
+    std::vector<int32_t> last_use;     // [S] global wave that last computes from the slot
+    int32_t cursor = 0;
+    int32_t next_wave = 0;             // next global wave index to hand out
+    uint32_t epoch = 1;
+
+    // enqueue progress
+    int32_t prefetched_upto = 0;       // global waves < this have their copies enqueued
+    int32_t forwarded_upto = 0;        // global waves < this have their compute enqueued
+    std::vector<hipEvent_t> ev_ready;  // ring: copies of wave g done
+    std::vector<hipEvent_t> ev_done;   // ring: compute of wave g done
+    std::vector<uint8_t> ready_recorded;  // ring: wave g recorded a ready event (it had misses)
+    bool events_made = false;
+
+    // kernel timing
+    bool profiling = false;
+    std::vector<sida::ProfRec> prof_pool;
+    size_t prof_used = 0;
+    double prof_ms[SIDA_K_COUNT] = {};
+    int64_t prof_n[SIDA_K_COUNT] = {};
+
+    int last_hip = 0;
+};
+
+namespace sida {
+
+// Host planner (plan.cpp).
+int plan_layer(sida_ctx *c, int32_t layer, const int32_t *ids, int32_t T, sida_plan *out);
+
+}  // namespace sida

@@ -1,0 +1,151 @@
+// K-a: token -> expert stable counting sort and permute-gather.
+//
+// Any implementation that invokes only the experts that have tokens (Section 2.2) must bring the
+// rows of one expert together.  The order is fixed as (expert id, token index) so that the result
+// is unique: perm[offsets[e] + j] is the j-th smallest token index routed to expert e.
+//
+// Three small launches plus the row gather:
+//   sort_hist   one wavefront per chunk of 256 tokens: LDS histogram of the chunk
+//   sort_scan   one workgroup: per-expert totals, exclusive scan over experts (offsets), and the
+//               first output row of every (chunk, expert) pair
+//   sort_rank   one wavefront per chunk: rank of a token among equal ids = (tokens of that id in
+//               earlier chunks) + (earlier rounds of this chunk) + (lower lanes of this round, by
+//               wavefront ballots over the 8 id bits)
+//   gather_rows one wavefront per output row, 16-byte accesses
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace sida {
+
+namespace {
+
+constexpr int kChunk = 256;      // tokens per wavefront (4 rounds of 64)
+constexpr int kMaxE = 256;
+
+__device__ __forceinline__ int clamp_id(int k, int E) { return k < 0 ? 0 : (k >= E ? E - 1 : k); }
+
+__global__ __launch_bounds__(64) void sort_hist(const int32_t *__restrict__ ids, int T, int E,
+                                                int32_t *__restrict__ block_hist)
+{
+    __shared__ int hist[kMaxE];
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += 64) hist[e] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kChunk;
+#pragma unroll
+    for (int r = 0; r < kChunk / 64; ++r) {
+        const int t = base + r * 64 + lane;
+        if (t < T) atomicAdd(&hist[clamp_id(ids[t], E)], 1);
+    }
+    __syncthreads();
+    for (int e = lane; e < E; e += 64) block_hist[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+// 256 threads, thread e owns expert e.
+__global__ __launch_bounds__(256) void sort_scan(int32_t *__restrict__ block_hist, int n_chunks, int E,
+                                                 int T, int32_t *__restrict__ counts,
+                                                 int32_t *__restrict__ offsets)
+{
+    __shared__ int wave_sum[4];
+    const int e = threadIdx.x;
+    int total = 0;
+    if (e < E)
+        for (int b = 0; b < n_chunks; ++b) total += block_hist[(size_t)b * E + e];
+
+    // exclusive scan of `total` over the 256 threads
+    int incl = total;
+    const int lane = e & 63, w = e >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_sum[w] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int i = 0; i < w; ++i) before += wave_sum[i];
+    const int excl = before + incl - total;
+
+    if (e < E) {
+        counts[e] = total;
+        offsets[e] = excl;
+        if (e == E - 1) offsets[E] = T;
+        int run = excl;
+        for (int b = 0; b < n_chunks; ++b) {
+            const size_t i = (size_t)b * E + e;
+            const int v = block_hist[i];
+            block_hist[i] = run;        // first output row of (chunk b, expert e)
+            run += v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids, int T, int E,
+                                                const int32_t *__restrict__ block_base,
+                                                int32_t *__restrict__ perm, int32_t *__restrict__ inv)
+{
+    __shared__ int next_row[kMaxE];
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += 64) next_row[e] = block_base[(size_t)blockIdx.x * E + e];
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int base = blockIdx.x * kChunk;
+#pragma unroll
+    for (int r = 0; r < kChunk / 64; ++r) {
+        const int t = base + r * 64 + lane;
+        const bool live = t < T;
+        const int k = live ? clamp_id(ids[t], E) : 0;
+        // lanes of this round that hold the same id
+        unsigned long long same = __ballot(live);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const unsigned long long b = __ballot((k >> bit) & 1);
+            same &= ((k >> bit) & 1) ? b : ~b;
+        }
+        if (live) {
+            const int ahead = __popcll(same & below);
+            const int row = next_row[k] + ahead;
+            perm[row] = t;
+            inv[t] = row;
+        }
+        __syncthreads();               // every lane has read next_row before anyone advances it
+        if (live && (same & below) == 0) next_row[k] += __popcll(same);
+        __syncthreads();
+    }
+}
+
+// One wavefront per output row; d*2 bytes per row moved as 16-byte pieces.
+__global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ x, const int32_t *__restrict__ perm,
+                                                   int T, int vec_per_row, uint4 *__restrict__ x_perm)
+{
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= T) return;
+    const int lane = threadIdx.x & 63;
+    const int t = perm[r];
+    const uint4 *src = x + (size_t)t * vec_per_row;
+    uint4 *dst = x_perm + (size_t)r * vec_per_row;
+    for (int i = lane; i < vec_per_row; i += 64) dst[i] = src[i];
+}
+
+}  // namespace
+
+int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32_t *offsets,
+                int32_t *block_hist, int32_t *perm, int32_t *inv, hipStream_t st)
+{
+    const int n_chunks = (T + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(sort_hist, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist);
+    hipLaunchKernelGGL(sort_scan, dim3(1), dim3(256), 0, st, block_hist, n_chunks, E, T, counts, offsets);
+    hipLaunchKernelGGL(sort_rank, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist, perm, inv);
+    return (int)hipGetLastError();
+}
+
+int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st)
+{
+    const int vec_per_row = d / 8;
+    hipLaunchKernelGGL(gather_rows, dim3((T + 3) / 4), dim3(256), 0, st, (const uint4 *)x, perm, T,
+                       vec_per_row, (uint4 *)x_perm);
+    return (int)hipGetLastError();
+}
+
+}  // namespace sida

@@ -1,0 +1,145 @@
+"""GPU parity of the whole layer path (plan -> prefetch -> sort/gather -> grouped FFN -> combine)
+against the oracle, through the C ABI, at sizes the oracle finishes in seconds."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2310_18859_amd as sm
+from gpu_util import (assert_close, bf16_tensor_to_f32, layer_inputs, make_runner, oracle_layer, say)
+from workloads import WORKLOADS, Workload, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def run_and_check(wl, reps=1, T_of=None, check_plan=True):
+    """Runs all layers `reps` times through sida_run_layers and checks every layer's y, its sort
+    outputs and its plan against the oracle."""
+    r = make_runner(wl)
+    st = oracle.PoolState(wl.E, wl.S)
+    worst = 0.0
+    for rep in range(reps):
+        ins = [layer_inputs(wl, l, None if T_of is None else T_of(l, rep)) for l in range(wl.L)]
+        plans = r.plan_all([i[1] for i in ins])
+        dev = [r.to_device(*i) for i in ins]
+        r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
+        r.sync()
+        for l in range(wl.L):
+            x_bits, ids, alpha = ins[l]
+            op = st.plan_layer(l, ids, wl.W)
+            p = plans[l]
+            if check_plan:
+                assert list(p.order)[:p.n_active] == op.order
+                assert list(p.slot)[:wl.E] == op.slot and list(p.wave)[:wl.E] == op.wave
+                assert list(p.hit)[:wl.E] == op.hit and list(p.wave_dep)[:p.n_waves] == op.wave_dep
+            y = bf16_tensor_to_f32(dev[l][3])
+            ref = oracle_layer(wl, r, l, x_bits, ids, alpha)
+            worst = max(worst, assert_close(y, ref, f"{wl.name} rep {rep} layer {l}"))
+    r.close()
+    return worst
+
+
+def test_config0_switch8_T256():
+    say("layer parity: config 0 (E=8, d=768, F=3072, T=256, all resident)")
+    err = run_and_check(WORKLOADS[0], reps=2)
+    say(f"  max rel err {err:.3e}")
+
+
+@pytest.mark.parametrize("name,L,E,d,F,T,zipf,S,W", [
+    ("ragged-small", 2, 5, 128, 256, 333, None, 5, 5),
+    ("one-token", 1, 4, 128, 128, 1, None, 2, 2),
+    ("tile-edges", 1, 3, 256, 384, 128 * 3 + 1, None, 3, 3),
+    ("waves-S3-W2", 3, 7, 128, 256, 500, 1.1, 3, 2),
+    ("thrash-S1-W1", 2, 6, 128, 128, 200, 1.0, 1, 1),
+    ("S2-W1", 2, 6, 128, 256, 257, 0.8, 2, 1),
+    ("S2-W2", 2, 6, 128, 256, 257, 0.8, 2, 2),
+    ("big-expert", 1, 4, 256, 512, 1500, 2.0, 4, 4),
+    ("E256", 1, 256, 128, 128, 4000, 0.8, 48, 24),
+])
+def test_small_shapes(name, L, E, d, F, T, zipf, S, W):
+    say(f"layer parity: {name}")
+    wl = Workload(100 + len(name), name, L, E, d, F, T, zipf, S, W)
+    err = run_and_check(wl, reps=2)
+    say(f"  max rel err {err:.3e}")
+
+
+def test_varying_T_including_empty_layers():
+    say("layer parity: T changes per call, some calls empty")
+    wl = Workload(120, "varT", 3, 6, 128, 256, 300, 1.0, 4, 2)
+    sizes = {(0, 0): 300, (1, 0): 0, (2, 0): 17, (0, 1): 1, (1, 1): 129, (2, 1): 0}
+    run_and_check(wl, reps=2, T_of=lambda l, rep: sizes[(l, rep)])
+
+
+def test_single_expert_is_a_dense_ffn():
+    say("layer parity: E=1")
+    run_and_check(Workload(130, "dense", 1, 1, 256, 512, 700, None, 1, 1))
+
+
+def test_identity_experts_unit_gates_bit_exact():
+    say("identity experts")
+    d, T, E = 128, 999, 5
+    wl = Workload(131, "identity", 1, E, d, d, T, None, E, E)
+    r = make_runner(wl)
+    eye = f32_to_bf16_bits(np.eye(d, dtype=np.float32)).reshape(-1)
+    hw = r.host_weights.numpy()
+    for e in range(E):
+        hw[e, :d * d] = eye
+        hw[e, d * d:] = eye
+    rng = np.random.default_rng(0)
+    x_bits = f32_to_bf16_bits(np.abs(rng.standard_normal((T, d))).astype(np.float32))
+    ids = rng.integers(0, E, T).astype(np.int32)
+    x, i, a, y = r.to_device(x_bits, ids, np.ones(T, np.float32))
+    plan = r.ctx.moe_plan(0, ids)
+    r.ctx.moe_layer_forward(plan, x, i, a, y, r.workspace, r.compute, r.copy)
+    r.sync()
+    assert np.array_equal(y.view(torch.uint16).cpu().numpy(), x_bits)
+    r.close()
+
+
+def test_replay_with_large_pool_hits_everything_and_repeats_y():
+    say("replay: second pass all hits")
+    wl = Workload(132, "replay", 3, 8, 128, 256, 400, 1.0, 24, 8)
+    r = make_runner(wl)
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    outs = []
+    for rep in range(2):
+        plans = r.plan_all([i[1] for i in ins])
+        assert all((p.n_miss == 0) == (rep == 1) for p in plans)
+        dev = [r.to_device(*i) for i in ins]
+        r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
+        r.sync()
+        outs.append([d[3].view(torch.uint16).cpu().numpy() for d in dev])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    r.close()
+
+
+def test_explicit_prefetch_then_forward_and_order_errors():
+    say("explicit prefetch / ordering errors")
+    wl = Workload(133, "order", 2, 6, 128, 128, 100, None, 6, 3)
+    r = make_runner(wl)
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    plans = r.plan_all([i[1] for i in ins])
+    dev = [r.to_device(*i) for i in ins]
+    with pytest.raises(sm.SidaError) as e:               # layer 1 before layer 0
+        r.ctx.moe_layer_forward(plans[1], *dev[1], r.workspace, r.compute, r.copy)
+    assert e.value.code == -3
+    with pytest.raises(sm.SidaError) as e:               # wave 1 before wave 0
+        r.ctx.expert_prefetch(plans[0], 1, r.copy)
+    assert e.value.code == -3
+    small = torch.zeros(256, dtype=torch.uint8, device=r.dev)
+    with pytest.raises(sm.SidaError) as e:
+        r.ctx.moe_layer_forward(plans[0], *dev[0], small, r.compute, r.copy)
+    assert e.value.code == -2
+    r.ctx.expert_prefetch(plans[0], 0, r.copy)           # the caller may prefetch ahead itself
+    r.ctx.expert_prefetch(plans[0], 0, r.copy)           # ... twice is a no-op
+    for l in range(wl.L):
+        r.ctx.moe_layer_forward(plans[l], *dev[l], r.workspace, r.compute, r.copy)
+    r.sync()
+    for l in range(wl.L):
+        ref = oracle_layer(wl, r, l, *ins[l])
+        assert_close(bf16_tensor_to_f32(dev[l][3]), ref, f"layer {l}")
+    with pytest.raises(sm.SidaError) as e:               # a plan is forwarded once
+        r.ctx.moe_layer_forward(plans[0], *dev[0], r.workspace, r.compute, r.copy)
+    assert e.value.code == -3
+    r.close()
