@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the SiDA-MoE layer hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: for each of the workload's L MoE layers,
+plan (host) -> expert prefetch host->HBM pool on the copy stream -> counting sort + gather ->
+grouped expert FFN per wave -> gate-weighted combine.  Token activations, ids and gate values are
+resident in HBM before the timed region; expert weights live in pinned host memory and stream
+through the S-slot pool, as the workload states.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+H2D_PEAK_GBS = 64.0            # PCIe Gen5 x16, one direction
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), see profiles/.
+# key: (workload name, mode, kernel) -> bytes per launch.  Empty until measured for that case.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_work(wl, plans_tokens):
+    """Per-token algorithmic bytes / flops of each kernel class ('Roofline accounting')."""
+    d, F = wl.d_model, wl.d_ff
+    return {
+        "sort": 4 * 2 + 8,                 # ids read by two passes, perm + inv written
+        "gather": 4 + 2 * d + 2 * d,       # perm, x row in, x_perm row out
+        "combine": 4 + 4 + 2 * d + 2 * d,  # inv, alpha, y_perm row in, y row out
+        "gemm1_flops": 2 * d * F,
+        "gemm2_flops": 2 * d * F,
+    }
+
+
+def time_steps(r, wl, dev, ids_host, steps, warmup, reset_each_step=False):
+    import torch
+    xs, idss, alphas, ys = ([d[i] for d in dev] for i in range(4))
+
+    def one_step():
+        plans = r.plan_all(ids_host)
+        r.run(plans, xs, idss, alphas, ys)
+        return plans
+
+    for _ in range(warmup):
+        one_step()
+    r.sync()
+    r.ctx.profile_read(reset=True)
+    t0 = time.perf_counter()
+    plans = None
+    for _ in range(steps):
+        plans = one_step()
+    r.sync()
+    dt = time.perf_counter() - t0
+    prof = r.ctx.profile_read(reset=True)
+    return dt, prof, plans
+
+
+def kernel_report(wl, prof, steps, n_miss_per_step):
+    """Average launch duration and achieved rate per kernel class."""
+    d, F, T, L = wl.d_model, wl.d_ff, wl.T, wl.L
+    tok = float(L * T * steps)             # tokens processed by each class over the timed region
+    out = {}
+    for k, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        e = {"launches": int(n), "avg_us": 1e3 * ms / n, "total_ms": ms}
+        s = ms * 1e-3
+        if k == "sort":
+            e["GBps"] = tok * 16 / s / 1e9
+        elif k == "gather":
+            e["GBps"] = tok * (4 + 4 * d) / s / 1e9
+        elif k == "combine":
+            e["GBps"] = tok * (8 + 4 * d) / s / 1e9
+        elif k in ("gemm1", "gemm2"):
+            e["TFLOPs"] = tok * 2 * d * F / s / 1e12
+            # bytes the launch must move at least: its experts' matrix once + activations in/out
+            w_bytes = n_miss_per_step["active_experts"] * steps * 2 * d * F
+            act = tok * (2 * d + 2 * F)
+            e["GBps_min_traffic"] = (w_bytes + act) / s / 1e9
+        elif k == "copy":
+            e["GBps"] = n_miss_per_step["loads"] * steps * 4 * d * F / s / 1e9
+        out[k] = e
+    return out
+
+
+def cpu_baseline(wl, r, ins, budget_tokens):
+    import oracle
+    x_bits, ids, alpha = ins[0]
+    n = min(budget_tokens, wl.T)
+    hw = r.host_weights.numpy()
+    blocks = [hw[e] for e in range(wl.E)]
+    t0 = time.perf_counter()
+    oracle.token_counts(ids[:n], wl.E)
+    oracle.moe_forward(x_bits[:n], ids[:n], alpha[:n], blocks, wl.d_model, wl.d_ff)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {n} tokens of layer 0 of {wl.name} (grouping + Eq. 1 per token), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=2, help="index into workloads.WORKLOADS (2 = Switch-base-128)")
+    ap.add_argument("--resident-steps", type=int, default=50)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with timing events")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle sample (0 = pick for ~15 s)")
+    ap.add_argument("--only", choices=["both", "streaming", "resident"], default="both")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2310_18859_amd.runner import MoERunner
+    from workloads import WORKLOADS, fill_host_weights, gen_gate, gen_ids, gen_x
+
+    wl = WORKLOADS[a.workload]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    # ---- streaming: the workload as stated (S-slot pool fed from pinned host memory) ----------
+    log(f"[bench] workload {wl.name}: L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T} S={wl.S} W={wl.W}")
+    r = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.S, wl.W, wl.T)
+    t0 = time.perf_counter()
+    fill_host_weights(wl, r.alloc_host_weights(), progress=lambda i, n: log(f"[bench] weights {i}/{n}"))
+    log(f"[bench] host weights: {wl.L * wl.E * wl.expert_bytes / 1e9:.2f} GB pinned in {time.perf_counter() - t0:.1f} s")
+    ins = [(gen_x(wl, l), gen_ids(wl, l), gen_gate(wl, l)) for l in range(wl.L)]
+    ids_host = [i[1] for i in ins]
+    dev = [r.to_device(*i) for i in ins]
+    r.sync()
+
+    result = {}
+    if a.only in ("both", "streaming"):
+        r.ctx.profile_enable(not a.no_profile)
+        dt, prof, plans = time_steps(r, wl, dev, ids_host, a.steps, a.warmup)
+        loads = sum(p.n_miss for p in plans)
+        active = sum(p.n_active for p in plans)
+        kern = kernel_report(wl, prof, a.steps, {"loads": loads, "active_experts": active})
+        result["streaming"] = {"dt": dt, "kernels": kern, "loads_per_step": loads,
+                               "waves_per_step": sum(p.n_waves for p in plans)}
+        log(f"[bench] streaming: {1e3 * dt / a.steps:.2f} ms/step, {loads} expert loads/step")
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        n = a.cpu_tokens or wl.T
+        log(f"[bench] timing the CPU oracle on {n} tokens ...")
+        cpu = cpu_baseline(wl, r, ins, n)
+        log(f"[bench] oracle: {cpu['value']:.1f} tokens/s on {cpu['cores']} threads")
+
+    # ---- resident: same kernels with every expert already in HBM (pool of L*E slots) -----------
+    if a.only in ("both", "resident"):
+        hw = r.host_weights
+        r.close()
+        r2 = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.L * wl.E, wl.E, wl.T)
+        r2.host_weights = hw
+        base = hw.data_ptr()
+        r2.ctx.bind_host_weights([base + i * r2.expert_bytes for i in range(wl.L * wl.E)], keep=hw)
+        dev2 = [r2.to_device(*i) for i in ins]
+        r2.ctx.profile_enable(False)
+        time_steps(r2, wl, dev2, ids_host, 1, 1)                 # first pass loads every activated expert
+        r2.ctx.profile_enable(not a.no_profile)
+        dt2, prof2, plans2 = time_steps(r2, wl, dev2, ids_host, a.resident_steps, 2)
+        assert sum(p.n_miss for p in plans2) == 0
+        active = sum(p.n_active for p in plans2)
+        kern2 = kernel_report(wl, prof2, a.resident_steps, {"loads": 0, "active_experts": active})
+        result["resident"] = {"dt": dt2, "kernels": kern2}
+        log(f"[bench] resident: {1e3 * dt2 / a.resident_steps:.3f} ms/step")
+        r2.close()
+
+    tokens_per_step = wl.L * wl.T
+    main_mode = "streaming" if "streaming" in result else "resident"
+    main_steps = a.steps if main_mode == "streaming" else a.resident_steps
+    main = result[main_mode]
+    line = {
+        "metric": "moe_layer_tokens_per_sec",
+        "value": tokens_per_step * main_steps / main["dt"],
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": main_steps, "warmup": a.warmup,
+        "ms_per_step": 1e3 * main["dt"] / main_steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "L": wl.L, "E": wl.E, "d_model": wl.d_model, "d_ff": wl.d_ff,
+                   "T": wl.T, "ids": f"zipf(s={wl.zipf_s})" if wl.zipf_s else "uniform",
+                   "pool_slots": wl.S if main_mode == "streaming" else wl.L * wl.E,
+                   "wave_experts": wl.W if main_mode == "streaming" else wl.E, "mode": main_mode},
+    }
+
+    def roofline_of(kern, mode):
+        if not kern or "gemm1" not in kern:
+            return None
+        k = "gemm1" if kern["gemm1"]["total_ms"] >= kern["gemm2"]["total_ms"] else "gemm2"
+        ach = kern[k]["TFLOPs"]
+        return {"kernel": f"grouped_gemm_nt<{'relu' if k == 'gemm1' else 'plain'}> ({k})", "bound": "mfma",
+                "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                "avg_launch_us": kern[k]["avg_us"],
+                "hbm_min_traffic_GBps": kern[k]["GBps_min_traffic"],
+                "hbm_min_traffic_frac": kern[k]["GBps_min_traffic"] / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC.get((wl.name, mode, k))}
+
+    line["roofline"] = roofline_of(main["kernels"], main_mode)
+    line["cpu_baseline"] = cpu
+    for mode in ("streaming", "resident"):
+        if mode not in result:
+            continue
+        st = a.steps if mode == "streaming" else a.resident_steps
+        e = {"tokens_per_s": tokens_per_step * st / result[mode]["dt"], "ms_per_step": 1e3 * result[mode]["dt"] / st,
+             "steps": st, "kernels": result[mode]["kernels"], "roofline": roofline_of(result[mode]["kernels"], mode)}
+        if mode == "streaming":
+            e["expert_loads_per_step"] = result[mode]["loads_per_step"]
+            e["waves_per_step"] = result[mode]["waves_per_step"]
+            h2d = result[mode]["loads_per_step"] * wl.expert_bytes * st / result[mode]["dt"] / 1e9
+            e["h2d"] = {"achieved": h2d, "peak": H2D_PEAK_GBS, "unit": "GB/s", "frac": h2d / H2D_PEAK_GBS,
+                        "note": "expert bytes copied per step / wall time per step"}
+        line[mode] = e
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
