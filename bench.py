@@ -122,6 +122,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with timing events")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle sample (0 = pick for ~15 s)")
     ap.add_argument("--only", choices=["both", "streaming", "resident"], default="both")
+    ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; 0 = as defined)")
+    ap.add_argument("--zipf", type=float, default=None, help="override the Zipf exponent (0 = uniform ids)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1")
@@ -132,6 +134,10 @@ def main():
     from workloads import WORKLOADS, fill_host_weights, gen_gate, gen_ids, gen_x
 
     wl = WORKLOADS[a.workload]
+    if a.tokens:
+        wl = wl.scaled(T=a.tokens, name=f"{wl.name}-T{a.tokens}")
+    if a.zipf is not None:
+        wl = wl.scaled(zipf_s=(a.zipf or None), name=f"{wl.name}-zipf{a.zipf}")
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 

@@ -39,7 +39,7 @@ class SidaPlan(C.Structure):
 
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
-                ("counts", "offsets", "block_hist", "perm", "inv", "x_perm", "h", "y_perm", "total")]
+                ("counts", "offsets", "block_hist", "perm", "inv", "x_perm", "h", "y_perm", "tiles", "sink", "total")]
 
 
 _LIB = None

@@ -30,7 +30,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", LIB] + os.environ.get("SIDA_EXTRA_HIPCC_FLAGS", "").split() + [os.path.join(CSRC, s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the gfx feature name and says so once per file: drop that line
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -37,6 +37,9 @@ int make_events(sida_ctx *c)
     return SIDA_OK;
 }
 
+// Upper bound of token tiles of a layer: every expert may end in a partial tile.
+size_t max_tiles(const sida_config &cfg, int32_t T) { return (size_t)T / kGemmTileM + (size_t)cfg.E + 1; }
+
 void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
 {
     const size_t n_chunks = ((size_t)T + kSortChunk - 1) / kSortChunk;
@@ -54,12 +57,17 @@ void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
     o->x_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
     o->h = take(2 * (size_t)T * (size_t)cfg.d_ff);
     o->y_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
+    o->tiles = take(sizeof(TileDesc) * max_tiles(cfg, T));
+    o->sink = take(kGemmSinkBytes);
     o->total = off;
 }
 
 struct Ws {
     int32_t *counts, *offsets, *block_hist, *perm, *inv;
     void *x_perm, *h, *y_perm;
+    TileDesc *tiles;
+    int32_t max_tiles;
+    void *sink;
 };
 
 Ws carve(const sida_config &cfg, int32_t T, void *base)
@@ -69,7 +77,8 @@ Ws carve(const sida_config &cfg, int32_t T, void *base)
     char *b = static_cast<char *>(base);
     return Ws{(int32_t *)(b + l.counts), (int32_t *)(b + l.offsets), (int32_t *)(b + l.block_hist),
               (int32_t *)(b + l.perm),   (int32_t *)(b + l.inv),     b + l.x_perm,
-              b + l.h,                   b + l.y_perm};
+              b + l.h,                   b + l.y_perm,               (TileDesc *)(b + l.tiles),
+              (int32_t)max_tiles(cfg, T), b + l.sink};
 }
 
 int check_plan(const sida_ctx *c, const sida_plan *p)
@@ -114,24 +123,37 @@ struct Timed {
     }
 };
 
-// The wave table of local wave w: the wave's experts, most tokens first (their tiles are
-// scheduled first so the long experts do not end up as the tail of the launch).
-void build_wave_table(const sida_plan *p, int32_t w, WaveTable *t)
+// Tile schedule of a layer: the activated experts wave by wave, inside a wave most tokens first,
+// and for every local wave the range of token tiles it owns in the expanded descriptor array.
+struct LayerSchedule {
+    LayerTable tbl;
+    int32_t tile_begin[SIDA_MAX_E];
+    int32_t m_tiles[SIDA_MAX_E];
+};
+
+void build_schedule(const sida_plan *p, LayerSchedule *s)
 {
-    const int32_t g = p->first_wave + w;
     int32_t idx[SIDA_MAX_E];
-    int32_t n = 0;
+    for (int32_t i = 0; i < p->n_active; ++i) idx[i] = p->order[i];     // already grouped by wave
+    std::stable_sort(idx, idx + p->n_active, [&](int32_t a, int32_t b) {
+        if (p->wave[a] != p->wave[b]) return p->wave[a] < p->wave[b];
+        return p->counts[a] > p->counts[b];
+    });
+    s->tbl.n = p->n_active;
+    for (int32_t w = 0; w < p->n_waves; ++w) s->tile_begin[w] = s->m_tiles[w] = 0;
+    int32_t at = 0, cur = -1;
     for (int32_t i = 0; i < p->n_active; ++i) {
-        const int32_t e = p->order[i];
-        if (p->wave[e] == g) idx[n++] = e;
-    }
-    std::stable_sort(idx, idx + n, [&](int32_t a, int32_t b) { return p->counts[a] > p->counts[b]; });
-    t->n = n;
-    t->m_tiles = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        t->expert[i] = (uint8_t)idx[i];
-        t->slot[i] = (int16_t)p->slot[idx[i]];
-        t->m_tiles += (p->counts[idx[i]] + kGemmTileM - 1) / kGemmTileM;
+        const int32_t e = idx[i];
+        s->tbl.expert[i] = (uint8_t)e;
+        s->tbl.slot[i] = (int16_t)p->slot[e];
+        const int32_t w = p->wave[e] - p->first_wave;
+        if (w != cur) {
+            s->tile_begin[w] = at;
+            cur = w;
+        }
+        const int32_t n_t = (p->counts[e] + kGemmTileM - 1) / kGemmTileM;
+        s->m_tiles[w] += n_t;
+        at += n_t;
     }
 }
 
@@ -188,19 +210,25 @@ int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, c
     return SIDA_OK;
 }
 
-int launch_wave_ffn(sida_ctx *c, const sida_plan *p, int32_t w, const Ws &ws, hipStream_t st)
+int launch_tiles(sida_ctx *c, const LayerSchedule &s, const Ws &ws, hipStream_t st)
 {
-    WaveTable tbl;
-    build_wave_table(p, w, &tbl);
+    Timed tm(c, SIDA_K_SORT, st);
+    HIP_TRY(c, (hipError_t)launch_build_tiles(s.tbl, ws.offsets, ws.tiles, ws.max_tiles, st));
+    return SIDA_OK;
+}
+
+int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws, hipStream_t st)
+{
+    const TileDesc *tiles = ws.tiles + s.tile_begin[w];
     {
         Timed tm(c, SIDA_K_GEMM1, st);
-        HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, ws.offsets, tbl,
-                                                c->cfg.d_model, c->cfg.d_ff, st));
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
+                                                c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
     }
     {
         Timed tm(c, SIDA_K_GEMM2, st);
-        HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, ws.offsets, tbl,
-                                                c->cfg.d_model, c->cfg.d_ff, st));
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
+                                                c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
     }
     return SIDA_OK;
 }
@@ -267,6 +295,10 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
         const Ws ws = carve(c->cfg, p->T, ws_dev);
         rc = launch_dispatch(c, a.x, a.ids, p->T, ws, compute);
         if (rc) return rc;
+        LayerSchedule sched;
+        build_schedule(p, &sched);
+        rc = launch_tiles(c, sched, ws, compute);
+        if (rc) return rc;
         for (int32_t w = 0; w < p->n_waves; ++w) {
             const int32_t g = p->first_wave + w;
             rc = try_prefetch(li, w);
@@ -279,7 +311,7 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
             }
             const int ring = g % kEventRing;
             if (c->ready_recorded[ring]) HIP_TRY(c, hipStreamWaitEvent(compute, c->ev_ready[ring], 0));
-            rc = launch_wave_ffn(c, p, w, ws, compute);
+            rc = launch_wave_ffn(c, sched, w, ws, compute);
             if (rc) return rc;
             if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_done[ring]));
             HIP_TRY(c, hipEventRecord(c->ev_done[ring], compute));
@@ -487,7 +519,12 @@ int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *wor
     if (!c->pool) return SIDA_ESTATE;
     rc = check_ws(c, plan->T, workspace_dev, workspace_bytes);
     if (rc) return rc;
-    return launch_wave_ffn(c, plan, wave, carve(c->cfg, plan->T, workspace_dev), static_cast<hipStream_t>(stream));
+    LayerSchedule sched;
+    build_schedule(plan, &sched);
+    const Ws ws = carve(c->cfg, plan->T, workspace_dev);
+    rc = launch_tiles(c, sched, ws, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    return launch_wave_ffn(c, sched, wave, ws, static_cast<hipStream_t>(stream));
 }
 
 int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, void *workspace_dev,

@@ -9,11 +9,23 @@
 // Both GEMMs are "NT": activations [M,K] and weights [N,K] are K-contiguous, so every MFMA
 // operand fragment (8 consecutive K values of one row) is one 16-byte access.
 //
-// Tiling: one workgroup (4 wavefronts, 2x2) computes a 128 (tokens) x 128 (weight rows) tile,
-// K in steps of 64 through double-buffered LDS; each wavefront owns 64x64 = 2x2 MFMA 32x32x16
-// tiles, fp32 accumulators.  The weight rows are fed as the MFMA's first operand and the token
-// rows as the second, so a lane ends up with 4 consecutive output columns of one token row and
-// stores them as one 8-byte piece.
+// The layer is bound by streaming each activated expert's weights from HBM once, so the kernel
+// is built to keep many bytes in flight per compute unit: tiles go global -> LDS directly
+// (global_load_lds, no register staging) through a ring of STAGES buffers, STAGES-1 K-steps
+// ahead of the MFMAs, with one workgroup barrier per K-step.
+//
+// Tiling: one workgroup of WM x WN wavefronts computes a BM (tokens) x BN (weight rows) tile, K in
+// steps of 64; each wavefront owns (BM/WM) x (BN/WN) as MFMA 32x32x16 tiles, fp32 accumulators.
+// Eight wavefronts per compute unit are needed to pull enough bytes per clock out of L2 with
+// direct-to-LDS loads (four reach about half of that).  The weight rows are the MFMA's first
+// operand and the token rows the second, so a lane ends up with 4 consecutive output columns of
+// one token row and stores them as one 8-byte piece.
+//
+// LDS tile layout: row r of a tile is 128 bytes (64 bf16); its 16-byte piece c is stored at
+// piece position c ^ (r & 7).  A direct-to-LDS load writes lane i's 16 bytes at offset 16*i of
+// the instruction's 1 KB window (8 rows), so lane i fetches global piece (i%8) ^ (i/8) of row i/8;
+// the MFMA fragment reads (32 rows, same logical piece) then touch 8 different positions per
+// 8 rows and are bank-conflict free without padding.
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -26,153 +38,254 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BM = kGemmTileM;   // token rows per tile
-constexpr int BN = 128;          // weight rows (output columns) per tile
 constexpr int BK = 64;           // K step
-constexpr int LDK = BK + 8;      // LDS row pitch in elements: 144 B keeps 16-byte reads conflict-free
-constexpr int kStageElems = (BM + BN) * LDK;
-constexpr int kLdsBytes = 2 * kStageElems * 2;
+constexpr int kRowBytes = BK * 2;
 
-template <bool RELU>
-__global__ __launch_bounds__(256) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
-                                                       const char *__restrict__ pool, size_t expert_bytes,
-                                                       size_t w_off, const int32_t *__restrict__ offsets,
-                                                       const WaveTable tbl, int N, int K)
+template <int N>
+__device__ __forceinline__ void wait_loads()
 {
-    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    __bf16 *lds = reinterpret_cast<__bf16 *>(lds_raw);
-    __shared__ int s_info[3];
-    __shared__ int s_wsum[4];
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int n_tiles_n = N / BN;
-    const int nt = blockIdx.x % n_tiles_n;
-    const int mt = blockIdx.x / n_tiles_n;
+__device__ __forceinline__ void load_to_lds(const void *gsrc, void *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
+}
 
-    // ---- which expert does token tile `mt` belong to?  thread i owns wave-table entry i ----
-    int my_off = 0, my_cnt = 0, my_tiles = 0;
-    if (tid < tbl.n) {
-        const int e = tbl.expert[tid];
-        my_off = offsets[e];
-        my_cnt = offsets[e + 1] - my_off;
-        my_tiles = (my_cnt + BM - 1) / BM;
-    }
-    int incl = my_tiles;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int v = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += v;
-    }
-    if (tid < 3) s_info[tid] = 0;
-    if (lane == 63) s_wsum[wv] = incl;
-    __syncthreads();
-    for (int i = 0; i < wv; ++i) incl += s_wsum[i];
-    const int excl = incl - my_tiles;
-    if (mt >= excl && mt < incl) {
-        const int local = mt - excl;
-        s_info[0] = tbl.slot[tid];
-        s_info[1] = my_off + local * BM;
-        s_info[2] = min(BM, my_cnt - local * BM);
-    }
-    __syncthreads();
-    const int rows = s_info[2];
-    if (rows <= 0) return;                                   // grid larger than the work: nothing to do
-    const int row0 = s_info[1];
-    const __bf16 *Wt = reinterpret_cast<const __bf16 *>(pool + (size_t)s_info[0] * expert_bytes + w_off) +
-                       (size_t)nt * BN * K;
-    const __bf16 *At = A + (size_t)row0 * K;
-
-    // ---- global -> LDS staging: 4 + 4 16-byte pieces per thread per K step ----
-    const int kc = (tid & 7) * 8;                            // K offset of this thread's pieces
-    int a_row[4], b_row[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (tid >> 3) + 32 * i;
-        a_row[i] = min(r, rows - 1);                         // rows past the end re-read the last valid row
-        b_row[i] = r;
-    }
-    bf16x8 ga[4], gb[4];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ga[i] = *reinterpret_cast<const bf16x8 *>(At + (size_t)a_row[i] * K + k0 + kc);
-            gb[i] = *reinterpret_cast<const bf16x8 *>(Wt + (size_t)b_row[i] * K + k0 + kc);
-        }
-    };
-    auto store_lds = [&](int buf) {
-        __bf16 *sa = lds + buf * kStageElems;
-        __bf16 *sb = sa + BM * LDK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (tid >> 3) + 32 * i;
-            *reinterpret_cast<bf16x8 *>(sa + r * LDK + kc) = ga[i];
-            *reinterpret_cast<bf16x8 *>(sb + r * LDK + kc) = gb[i];
-        }
-    };
-
-    const int wm = wv & 1, wn = wv >> 1;                     // wavefront position in the 2x2 grid
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int nk = K / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const __bf16 *sa = lds + buf * kStageElems + (wm * 64 + frag_row) * LDK + frag_k;
-        const __bf16 *sb = lds + buf * kStageElems + BM * LDK + (wn * 64 + frag_row) * LDK + frag_k;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 xf[2], wf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                xf[i] = *reinterpret_cast<const bf16x8 *>(sa + i * 32 * LDK + kk);
-                wf[i] = *reinterpret_cast<const bf16x8 *>(sb + i * 32 * LDK + kk);
-            }
-#pragma unroll
-            for (int in = 0; in < 2; ++in)
-#pragma unroll
-                for (int im = 0; im < 2; ++im)
-                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[in], xf[im], acc[in][im], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4 ----
-    const int half = lane >> 5;
-#pragma unroll
-    for (int im = 0; im < 2; ++im) {
-        const int m = wm * 64 + im * 32 + frag_row;
-        if (m >= rows) continue;
-        __bf16 *crow = C + (size_t)(row0 + m) * N + (size_t)nt * BN + wn * 64;
-#pragma unroll
-        for (int in = 0; in < 2; ++in)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                bf16x4 o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float v = acc[in][im][q * 4 + j];
-                    if (RELU) v = v > 0.f ? v : 0.f;
-                    o[j] = (__bf16)v;
-                }
-                *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
-            }
+// Waits until at most ahead*LOADS of this thread's direct loads are outstanding (ahead <= MAXA).
+template <int LOADS, int MAXA>
+__device__ __forceinline__ void wait_ahead(int ahead)
+{
+    if constexpr (MAXA == 0) {
+        wait_loads<0>();
+    } else {
+        if (ahead >= MAXA) wait_loads<MAXA * LOADS>();
+        else wait_ahead<LOADS, MAXA - 1>(ahead);
     }
 }
 
+constexpr int BM = kGemmTileM;    // token rows per tile
+constexpr int BN = 128;           // weight rows (output columns) per tile
+constexpr int WM = 2, WN = 4;     // wavefront grid of a workgroup
+constexpr int NW = WM * WN;
+constexpr int STAGES = 4;
+constexpr int kStageBytes = (BM + BN) * kRowBytes;
+constexpr int kLdsBytes = STAGES * kStageBytes;
+constexpr int A_LOADS = BM / (8 * NW);      // direct loads per thread per K-step, token tile
+constexpr int B_LOADS = BN / (8 * NW);      //   ... weight tile
+constexpr int LOADS = A_LOADS + B_LOADS;
+constexpr int MI = BM / (32 * WM);          // 32-row MFMA blocks per wavefront along tokens
+constexpr int NI = BN / (32 * WN);          //   ... along weight rows
+static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile");
+static_assert((STAGES - 2) * LOADS <= 63, "vmcnt range");
+
+// Output tile t of a launch -> (token tile, weight-row tile).  Workgroup b runs on XCD b % 8
+// (round-robin dispatch), every XCD has its own L2, and a persistent workgroup takes tiles
+// b, b+G, b+2G, ... with G a multiple of 8, so tile t is always computed on XCD t % 8.  Each XCD is
+// given whole token tiles: its consecutive tiles walk the weight-row tiles of one token tile, so
+// the token rows are fetched into that L2 once and reused n_tiles_n times.
+__device__ __forceinline__ void map_tile(int t, int m_tiles, int n_tiles_n, int *mt, int *nt)
+{
+    const int full = (m_tiles / 8) * 8;                       // token tiles in complete groups of 8
+    if (t < full * n_tiles_n) {
+        const int xcd = t & 7, local = t >> 3;
+        *mt = (local / n_tiles_n) * 8 + xcd;
+        *nt = local % n_tiles_n;
+    } else {                                                  // the last (< 8) token tiles: plain order
+        const int rest = t - full * n_tiles_n;
+        *mt = full + rest / n_tiles_n;
+        *nt = rest % n_tiles_n;
+    }
+}
+
+// Persistent workgroups: one per compute unit, each walks its tiles t = b, b+G, ... and treats
+// (tile, K-step) as ONE stream of stages.  The loads run STAGES-1 stages ahead of the MFMAs also
+// across tile boundaries, so the memory pipe does not drain between tiles.
 template <bool RELU>
-int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const int32_t *offsets,
-           const WaveTable &tbl, int N, int K, hipStream_t st)
+__global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
+                                                           const char *__restrict__ pool, size_t expert_bytes,
+                                                           size_t w_off, const TileDesc *__restrict__ tiles,
+                                                           int m_tiles, int N, int K, char *__restrict__ sink)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_tiles_n = N / BN;
+    const int total = m_tiles * n_tiles_n;
+    const int G = gridDim.x;
+    if ((int)blockIdx.x >= total) return;
+    const int my_tiles = (total - (int)blockIdx.x + G - 1) / G;
+    const int nk = K / BK;
+    const int steps = my_tiles * nk;
+
+    // ---- load side: lane i of a direct load covers row i/8 of its 8-row window, stored piece i%8 ----
+    const int sub_row = lane >> 3;
+    const int piece = (lane & 7) ^ sub_row;                   // logical 16-byte piece this lane fetches
+    // Half of the wavefronts fetch only weight rows (HBM latency), the other half only token rows
+    // (mostly L2 hits): a wavefront's loads complete in issue order, so mixing the two kinds in
+    // one wavefront would make the fast loads wait behind the slow ones.
+    static_assert(BM == BN && NW % 2 == 0 && LOADS * 8 * (NW / 2) == BM, "load split");
+    const bool loads_tokens = wv >= NW / 2;
+    const int lw = wv % (NW / 2);
+    const char *src[LOADS];
+    int ld_tile = blockIdx.x, ld_k = 0, issued = 0;
+    int ld_row0 = 0, ld_rows = 0, ld_nt = 0;                  // tile the load side works on
+    auto aim = [&](int t) {                                   // point the load side at tile t
+        int mt, nt;
+        map_tile(t, m_tiles, n_tiles_n, &mt, &nt);
+        const TileDesc td = tiles[mt];                        // uniform address: a scalar load
+        ld_row0 = td.row0;
+        ld_rows = td.rows;
+        ld_nt = nt;
+        const char *Wt = pool + (size_t)td.slot * expert_bytes + w_off + (size_t)nt * BN * K * 2;
+        const char *At = reinterpret_cast<const char *>(A) + (size_t)td.row0 * K * 2;
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int r = (lw * LOADS + j) * 8 + sub_row;
+            src[j] = loads_tokens ? At + (size_t)min(r, td.rows - 1) * K * 2 + piece * 16   // rows past the end
+                                  : Wt + (size_t)r * K * 2 + piece * 16;                    // re-read the last one
+        }
+    };
+    auto issue = [&]() {                                      // next stage of the stream
+        char *dst = lds + (issued % STAGES) * kStageBytes + (loads_tokens ? 0 : BM * kRowBytes);
+        const size_t koff = (size_t)ld_k * kRowBytes;
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) load_to_lds(src[j] + koff, dst + (lw * LOADS + j) * 1024);
+        ++issued;
+        if (++ld_k == nk) {
+            ld_k = 0;
+            ld_tile += G;
+            if (issued < steps) aim(ld_tile);
+        }
+    };
+
+    // ---- compute side ----
+    const int wm = wv % WM, wn = wv / WM;                     // wavefront position in the WM x WN grid
+    const int frag_row = lane & 31, half = lane >> 5;
+    const int sw = frag_row & 7;
+    int x_off[MI], w_off_l[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) x_off[i] = (wm * (BM / WM) + i * 32 + frag_row) * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) w_off_l[i] = BM * kRowBytes + (wn * (BN / WN) + i * 32 + frag_row) * kRowBytes;
+    f32x16 acc[NI][MI];
+    auto clear = [&]() {
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < MI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+    clear();
+    constexpr int STORES = MI * NI * 4;                       // result stores per thread per tile
+    // The loads are at most one tile ahead of the MFMAs when a tile has at least STAGES-1 K-steps;
+    // then the compute side can take each tile's coordinates over from the load side.
+    const bool handover = nk >= STAGES - 1;
+    int cp_tile = blockIdx.x, cp_k = 0, boost = 0;
+
+    aim(ld_tile);
+    int cp_row0 = ld_row0, cp_rows = ld_rows, cp_nt = ld_nt;  // tile the compute side works on
+    int nx_row0 = 0, nx_rows = 0, nx_nt = 0;
+    for (int s = 0; s < STAGES - 1 && s < steps; ++s) {
+        issue();
+        if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
+    }
+
+    for (int step = 0; step < steps; ++step) {
+        // stages step .. step+STAGES-2 are in flight (fewer at the very end); stage `step` must have landed
+        // For the STAGES-1 steps after a tile's result stores those may be outstanding too (vector
+        // memory operations of a wavefront complete in issue order, stores included).
+        const int ahead = min(steps - 1 - step, STAGES - 2);
+        if (boost > 0 && ahead == STAGES - 2) wait_loads<(STAGES - 2) * LOADS + STORES>();
+        else wait_ahead<LOADS, STAGES - 2>(ahead);
+        if (boost > 0) --boost;
+        __builtin_amdgcn_s_barrier();                         // everyone's pieces of this stage are in LDS, and
+                                                              // everyone is done reading the stage refilled next
+        if (issued < steps) {
+            issue();
+            if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
+        }
+
+        const char *st = lds + (step % STAGES) * kStageBytes;
+        // MFMA operand fragments are fetched one K sub-step ahead of the MFMAs that use them, so
+        // the LDS latency is covered by matrix work
+        bf16x8 xf[2][MI], wf[2][NI];
+        auto fetch = [&](int ks, int into) {
+            const int pos = ((ks * 2 + half) ^ sw) * 16;
+#pragma unroll
+            for (int i = 0; i < MI; ++i) xf[into][i] = *reinterpret_cast<const bf16x8 *>(st + x_off[i] + pos);
+#pragma unroll
+            for (int i = 0; i < NI; ++i) wf[into][i] = *reinterpret_cast<const bf16x8 *>(st + w_off_l[i] + pos);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
+#pragma unroll
+            for (int in = 0; in < NI; ++in)
+#pragma unroll
+                for (int im = 0; im < MI; ++im)
+                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][in], xf[ks & 1][im], acc[in][im],
+                                                                         0, 0, 0);
+        }
+
+        if (++cp_k == nk) {
+            // ---- tile done: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4.
+            // Every thread issues all its stores (the wait above counts them): rows past the end of
+            // the tile go to a scratch sink instead of C.
+            if (!handover) {
+                int mt;
+                map_tile(cp_tile, m_tiles, n_tiles_n, &mt, &cp_nt);
+                const TileDesc td = tiles[mt];
+                cp_row0 = td.row0;
+                cp_rows = td.rows;
+            }
+#pragma unroll
+            for (int im = 0; im < MI; ++im) {
+                const int m = wm * (BM / WM) + im * 32 + frag_row;
+                __bf16 *crow = m < cp_rows
+                                   ? C + (size_t)(cp_row0 + m) * N + (size_t)cp_nt * BN + wn * (BN / WN)
+                                   : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * (NI * 32);
+#pragma unroll
+                for (int in = 0; in < NI; ++in)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            float v = acc[in][im][q * 4 + j];
+                            if (RELU) v = v > 0.f ? v : 0.f;
+                            o[j] = (__bf16)v;
+                        }
+                        *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
+                    }
+            }
+            if (handover) { cp_row0 = nx_row0; cp_rows = nx_rows; cp_nt = nx_nt; }
+            boost = nk >= STAGES ? STAGES - 1 : 0;
+            clear();
+            cp_k = 0;
+            cp_tile += G;
+        }
+    }
+}
+
+int persistent_grid()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+        cus = prop.multiProcessorCount > 0 ? (prop.multiProcessorCount + 7) / 8 * 8 : 256;
+    }
+    return cus;
+}
+
+template <bool RELU>
+int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
+           int32_t m_tiles, int N, int K, void *sink, hipStream_t st)
 {
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
@@ -181,25 +294,72 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    if (tbl.m_tiles <= 0) return 0;
-    const unsigned grid = (unsigned)tbl.m_tiles * (unsigned)(N / BN);
-    hipLaunchKernelGGL(grouped_gemm_nt<RELU>, dim3(grid), dim3(256), kLdsBytes, st, (const __bf16 *)A, (__bf16 *)C,
-                       pool, expert_bytes, w_off, offsets, tbl, N, K);
+    if (m_tiles <= 0) return 0;
+    const int total = m_tiles * (N / BN);
+    const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
+    hipLaunchKernelGGL((grouped_gemm_nt<RELU>), dim3(grid), dim3(NW * 64), kLdsBytes, st, (const __bf16 *)A, (__bf16 *)C,
+                       pool, expert_bytes, w_off, tiles, m_tiles, N, K, (char *)sink);
     return (int)hipGetLastError();
 }
 
 }  // namespace
 
-int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const int32_t *offsets,
-                     const WaveTable &tbl, int32_t d, int32_t F, hipStream_t st)
+int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
+                     int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
-    return launch<true>(x_perm, h, pool, expert_bytes, 0, offsets, tbl, F, d, st);
+    return launch<true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, F, d, sink, st);
 }
 
-int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const int32_t *offsets,
-                     const WaveTable &tbl, int32_t d, int32_t F, hipStream_t st)
+int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
+                     int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
-    return launch<false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, offsets, tbl, d, F, st);
+    return launch<false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles, d, F, sink, st);
+}
+
+// ---- token-tile descriptors ----------------------------------------------------------------
+namespace {
+
+// One workgroup; thread i owns table entry i.
+__global__ __launch_bounds__(256) void build_tiles(const LayerTable tbl, const int32_t *__restrict__ offsets,
+                                                   TileDesc *__restrict__ tiles, int max_tiles)
+{
+    __shared__ int s_wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    int e = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
+    if (tid < tbl.n) {
+        e = tbl.expert[tid];
+        slot = tbl.slot[tid];
+        off = offsets[e];
+        cnt = offsets[e + 1] - off;
+        n_t = (cnt + kGemmTileM - 1) / kGemmTileM;
+    }
+    int incl = n_t;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) s_wsum[wv] = incl;
+    __syncthreads();
+    for (int i = 0; i < wv; ++i) incl += s_wsum[i];
+    int at = incl - n_t;
+    for (int k = 0; k < n_t && at < max_tiles; ++k, ++at) {
+        TileDesc t;
+        t.slot = slot;
+        t.row0 = off + k * kGemmTileM;
+        t.rows = min(kGemmTileM, cnt - k * kGemmTileM);
+        t.expert = e;
+        tiles[at] = t;
+    }
+}
+
+}  // namespace
+
+int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
+                       hipStream_t st)
+{
+    hipLaunchKernelGGL(build_tiles, dim3(1), dim3(256), 0, st, tbl, offsets, tiles, max_tiles);
+    return (int)hipGetLastError();
 }
 
 }  // namespace sida

@@ -6,13 +6,21 @@
 
 namespace sida {
 
-// Experts of one wave in the order their tiles are scheduled (largest first), passed to the
-// grouped GEMM kernels by value as a kernel argument.
-struct WaveTable {
-    int32_t n;                 // experts in the wave
-    int32_t m_tiles;           // sum over the wave's experts of ceil(count / tile rows)
+// The activated experts of one layer in the order their token tiles are scheduled: wave by wave,
+// inside a wave the expert with the most tokens first (so the long experts do not end up as the
+// tail of a launch).  Passed by value to the kernel that expands it into token-tile descriptors.
+struct LayerTable {
+    int32_t n;                 // activated experts
     int16_t slot[256];         // pool slot of entry i
     uint8_t expert[256];       // expert id of entry i
+};
+
+// One token tile of the grouped GEMMs: up to kGemmTileM consecutive rows of one expert.
+struct TileDesc {
+    int32_t slot;              // pool slot holding the expert's weights
+    int32_t row0;              // first row in x_perm / h / y_perm
+    int32_t rows;              // 1..kGemmTileM
+    int32_t expert;
 };
 
 // K-a: stable counting sort of T tokens by expert id.
@@ -22,14 +30,21 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
 // K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
+// tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles).
+// sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
-                     const int32_t *offsets, const WaveTable &tbl, int32_t d, int32_t F, hipStream_t st);
+                     const TileDesc *tiles, int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
-                     const int32_t *offsets, const WaveTable &tbl, int32_t d, int32_t F, hipStream_t st);
+                     const TileDesc *tiles, int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st);
+// Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
+// entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
+int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
+                       hipStream_t st);
 // K-c: y[t,:] = alpha[t] * y_perm[inv[t],:].
 int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, int32_t T, int32_t d,
                    void *y, hipStream_t st);
 
+constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)
 
 }  // namespace sida

@@ -130,7 +130,7 @@ def test_error_paths_leave_state_untouched():
 def test_workspace_layout_is_aligned_and_ordered():
     ctx = sm.Context(1, 64, 768, 3072, 8, 8, 5000)
     lay = ctx.workspace_layout(4999)
-    offs = [lay.counts, lay.offsets, lay.block_hist, lay.perm, lay.inv, lay.x_perm, lay.h, lay.y_perm, lay.total]
+    offs = [lay.counts, lay.offsets, lay.block_hist, lay.perm, lay.inv, lay.x_perm, lay.h, lay.y_perm, lay.tiles, lay.sink, lay.total]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lay.h - lay.x_perm >= 4999 * 768 * 2 and lay.y_perm - lay.h >= 4999 * 3072 * 2
     assert lay.total == ctx.workspace_bytes(4999)
