@@ -129,6 +129,7 @@ struct LayerSchedule {
     LayerTable tbl;
     int32_t tile_begin[SIDA_MAX_E];
     int32_t m_tiles[SIDA_MAX_E];
+    int32_t m_tall[SIDA_MAX_E];       // leading tiles of the wave that belong to experts with > kGemmTileM tokens
 };
 
 void build_schedule(const sida_plan *p, LayerSchedule *s)
@@ -140,7 +141,7 @@ void build_schedule(const sida_plan *p, LayerSchedule *s)
         return p->counts[a] > p->counts[b];
     });
     s->tbl.n = p->n_active;
-    for (int32_t w = 0; w < p->n_waves; ++w) s->tile_begin[w] = s->m_tiles[w] = 0;
+    for (int32_t w = 0; w < p->n_waves; ++w) s->tile_begin[w] = s->m_tiles[w] = s->m_tall[w] = 0;
     int32_t at = 0, cur = -1;
     for (int32_t i = 0; i < p->n_active; ++i) {
         const int32_t e = idx[i];
@@ -153,6 +154,7 @@ void build_schedule(const sida_plan *p, LayerSchedule *s)
         }
         const int32_t n_t = (p->counts[e] + kGemmTileM - 1) / kGemmTileM;
         s->m_tiles[w] += n_t;
+        if (n_t > 1) s->m_tall[w] += n_t;                            // sorted by count: these come first
         at += n_t;
     }
 }
@@ -223,12 +225,12 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
     {
         Timed tm(c, SIDA_K_GEMM1, st);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
     }
     {
         Timed tm(c, SIDA_K_GEMM2, st);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
     }
     return SIDA_OK;
 }

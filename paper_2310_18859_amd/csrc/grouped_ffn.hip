@@ -65,36 +65,43 @@ __device__ __forceinline__ void wait_ahead(int ahead)
     }
 }
 
-constexpr int BM = kGemmTileM;    // token rows per tile
-constexpr int BN = 128;           // weight rows (output columns) per tile
-constexpr int WM = 2, WN = 4;     // wavefront grid of a workgroup
-constexpr int NW = WM * WN;
-constexpr int STAGES = 4;
-constexpr int kStageBytes = (BM + BN) * kRowBytes;
-constexpr int kLdsBytes = STAGES * kStageBytes;
-constexpr int A_LOADS = BM / (8 * NW);      // direct loads per thread per K-step, token tile
-constexpr int B_LOADS = BN / (8 * NW);      //   ... weight tile
-constexpr int LOADS = A_LOADS + B_LOADS;
-constexpr int MI = BM / (32 * WM);          // 32-row MFMA blocks per wavefront along tokens
-constexpr int NI = BN / (32 * WN);          //   ... along weight rows
-static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile");
-static_assert((STAGES - 2) * LOADS <= 63, "vmcnt range");
-
-// Output tile t of a launch -> (token tile, weight-row tile).  Workgroup b runs on XCD b % 8
-// (round-robin dispatch), every XCD has its own L2, and a persistent workgroup takes tiles
-// b, b+G, b+2G, ... with G a multiple of 8, so tile t is always computed on XCD t % 8.  Each XCD is
-// given whole token tiles: its consecutive tiles walk the weight-row tiles of one token tile, so
-// the token rows are fetched into that L2 once and reused n_tiles_n times.
-__device__ __forceinline__ void map_tile(int t, int m_tiles, int n_tiles_n, int *mt, int *nt)
+// Output tile t of a launch -> (token tile, weight-row tile).
+//
+// What decides the speed is the number of bytes that miss the L2: every XCD has its own 4 MiB L2,
+// and whatever misses it (HBM or Infinity Cache alike) arrives at ~6.5 TB/s over all XCDs, a
+// third of the L2-hit rate.  Workgroup b runs on XCD b % 8 (round-robin dispatch) and a persistent
+// workgroup takes tiles b, b+G, b+2G, ... with G a multiple of 8, so tile t is computed on XCD
+// t % 8, and the 32 compute units of an XCD work on 32 consecutive tiles of that XCD's sequence at
+// any time.  The sequence is built from groups of 4 consecutive token tiles (the list is sorted by
+// expert, most tokens first), dealt round-robin to the XCDs:
+//  * a group inside one many-token expert is walked as 4 x nw blocks (4 token tiles x nw weight-row
+//    tiles): the 32 concurrent tiles share 4 token tiles and nw weight tiles, so the expert's
+//    weights enter this L2 once per group instead of once per token tile;
+//  * any other group (few-token experts, all with different weights) is walked token tile by token
+//    tile, so a token tile is fetched once and used by all its weight-row tiles at the same time.
+// Groups that do not fill a complete round of 8, and the last (< 4) token tiles, follow in plain
+// order.  The mapping is a bijection on [0, m_tiles * n_tiles_n).
+__device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_tiles_n, int nw, int *mt, int *nt)
 {
-    const int full = (m_tiles / 8) * 8;                       // token tiles in complete groups of 8
-    if (t < full * n_tiles_n) {
+    const int per_group = 4 * n_tiles_n;
+    const int rounds = (m_tiles / 4) / 8;                     // complete rounds of 8 groups
+    const int sym = rounds * 8 * per_group;
+    if (t < sym) {
         const int xcd = t & 7, local = t >> 3;
-        *mt = (local / n_tiles_n) * 8 + xcd;
-        *nt = local % n_tiles_n;
-    } else {                                                  // the last (< 8) token tiles: plain order
-        const int rest = t - full * n_tiles_n;
-        *mt = full + rest / n_tiles_n;
+        const int group = (local / per_group) * 8 + xcd;
+        const int r = local % per_group;
+        const int first = group * 4;
+        if (first + 4 <= m_tall) {                            // inside many-token experts: 4 x nw blocks
+            const int rr = r % (4 * nw);
+            *mt = first + rr / nw;
+            *nt = (r / (4 * nw)) * nw + rr % nw;
+        } else {
+            *mt = first + r / n_tiles_n;
+            *nt = r % n_tiles_n;
+        }
+    } else {
+        const int rest = t - sym;
+        *mt = rounds * 32 + rest / n_tiles_n;
         *nt = rest % n_tiles_n;
     }
 }
@@ -102,12 +109,25 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int n_tiles_n, int 
 // Persistent workgroups: one per compute unit, each walks its tiles t = b, b+G, ... and treats
 // (tile, K-step) as ONE stream of stages.  The loads run STAGES-1 stages ahead of the MFMAs also
 // across tile boundaries, so the memory pipe does not drain between tiles.
-template <bool RELU>
-__global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
-                                                           const char *__restrict__ pool, size_t expert_bytes,
-                                                           size_t w_off, const TileDesc *__restrict__ tiles,
-                                                           int m_tiles, int N, int K, char *__restrict__ sink)
+//
+// BM x BN is the output tile (tokens x weight rows), WM x WN the wavefront grid (8 wavefronts).
+template <int BM, int BN, int WM, int WN, int STAGES, bool RELU>
+__global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
+                                                               const char *__restrict__ pool, size_t expert_bytes,
+                                                               size_t w_off, const TileDesc *__restrict__ tiles,
+                                                               int m_tiles, int m_tall, int nw, int N, int K,
+                                                               char *__restrict__ sink)
 {
+    constexpr int NW = WM * WN;
+    constexpr int kStageBytes = (BM + BN) * kRowBytes;
+    constexpr int LOADS = (BM + BN) / (8 * NW);               // direct loads per thread per K-step
+    constexpr int MI = BM / (32 * WM);                        // 32-row MFMA blocks per wavefront along tokens
+    constexpr int NI = BN / (32 * WN);                        //   ... along weight rows
+    constexpr int STORES = MI * NI * 4;                       // result stores per thread per tile
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM + BN) % (8 * NW) == 0 && BM % 8 == 0, "tile");
+    static_assert(STAGES >= 2 && (STAGES - 2) * LOADS + STORES <= 63, "vmcnt range");
+    static_assert(NW * 64 * NI * 64 <= kGemmSinkBytes, "sink size");
+
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -122,18 +142,14 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restr
     // ---- load side: lane i of a direct load covers row i/8 of its 8-row window, stored piece i%8 ----
     const int sub_row = lane >> 3;
     const int piece = (lane & 7) ^ sub_row;                   // logical 16-byte piece this lane fetches
-    // Half of the wavefronts fetch only weight rows (HBM latency), the other half only token rows
-    // (mostly L2 hits): a wavefront's loads complete in issue order, so mixing the two kinds in
-    // one wavefront would make the fast loads wait behind the slow ones.
-    static_assert(BM == BN && NW % 2 == 0 && LOADS * 8 * (NW / 2) == BM, "load split");
-    const bool loads_tokens = wv >= NW / 2;
-    const int lw = wv % (NW / 2);
+    // A stage is BM token rows followed by BN weight rows, 128 bytes each; direct load number i of
+    // a stage fills rows 8i .. 8i+7 (1 KiB); wavefront w issues loads w*LOADS .. w*LOADS+LOADS-1.
     const char *src[LOADS];
     int ld_tile = blockIdx.x, ld_k = 0, issued = 0;
     int ld_row0 = 0, ld_rows = 0, ld_nt = 0;                  // tile the load side works on
     auto aim = [&](int t) {                                   // point the load side at tile t
         int mt, nt;
-        map_tile(t, m_tiles, n_tiles_n, &mt, &nt);
+        map_tile(t, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
         const TileDesc td = tiles[mt];                        // uniform address: a scalar load
         ld_row0 = td.row0;
         ld_rows = td.rows;
@@ -142,16 +158,16 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restr
         const char *At = reinterpret_cast<const char *>(A) + (size_t)td.row0 * K * 2;
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
-            const int r = (lw * LOADS + j) * 8 + sub_row;
-            src[j] = loads_tokens ? At + (size_t)min(r, td.rows - 1) * K * 2 + piece * 16   // rows past the end
-                                  : Wt + (size_t)r * K * 2 + piece * 16;                    // re-read the last one
+            const int r = (wv * LOADS + j) * 8 + sub_row;     // row in the stage
+            src[j] = r < BM ? At + (size_t)(r % td.rows) * K * 2 + piece * 16    // rows past the end wrap around
+                            : Wt + (size_t)(r - BM) * K * 2 + piece * 16;        // (spread over all valid rows)
         }
     };
     auto issue = [&]() {                                      // next stage of the stream
-        char *dst = lds + (issued % STAGES) * kStageBytes + (loads_tokens ? 0 : BM * kRowBytes);
+        char *dst = lds + (issued % STAGES) * kStageBytes + wv * LOADS * 1024;
         const size_t koff = (size_t)ld_k * kRowBytes;
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) load_to_lds(src[j] + koff, dst + (lw * LOADS + j) * 1024);
+        for (int j = 0; j < LOADS; ++j) load_to_lds(src[j] + koff, dst + j * 1024);
         ++issued;
         if (++ld_k == nk) {
             ld_k = 0;
@@ -179,7 +195,6 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restr
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     };
     clear();
-    constexpr int STORES = MI * NI * 4;                       // result stores per thread per tile
     // The loads are at most one tile ahead of the MFMAs when a tile has at least STAGES-1 K-steps;
     // then the compute side can take each tile's coordinates over from the load side.
     const bool handover = nk >= STAGES - 1;
@@ -237,7 +252,7 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_nt(const __bf16 *__restr
             // the tile go to a scratch sink instead of C.
             if (!handover) {
                 int mt;
-                map_tile(cp_tile, m_tiles, n_tiles_n, &mt, &cp_nt);
+                map_tile(cp_tile, m_tiles, m_tall, n_tiles_n, nw, &mt, &cp_nt);
                 const TileDesc td = tiles[mt];
                 cp_row0 = td.row0;
                 cp_rows = td.rows;
@@ -283,37 +298,44 @@ int persistent_grid()
     return cus;
 }
 
-template <bool RELU>
+template <int BM, int BN, int WM, int WN, int STAGES, bool RELU>
 int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
-           int32_t m_tiles, int N, int K, void *sink, hipStream_t st)
+           int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, hipStream_t st)
 {
+    constexpr int kLdsBytes = STAGES * (BM + BN) * kRowBytes;
+    static_assert(kLdsBytes <= 160 * 1024, "LDS");
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<RELU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, BN, WM, WN, STAGES, RELU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
     if (m_tiles <= 0) return 0;
-    const int total = m_tiles * (N / BN);
+    const int n_tiles_n = N / BN;
+    int nw = n_tiles_n < 8 ? n_tiles_n : 8;                  // weight-row tiles per block of a many-token group
+    while (n_tiles_n % nw) --nw;
+    const int total = m_tiles * n_tiles_n;
     const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
-    hipLaunchKernelGGL((grouped_gemm_nt<RELU>), dim3(grid), dim3(NW * 64), kLdsBytes, st, (const __bf16 *)A, (__bf16 *)C,
-                       pool, expert_bytes, w_off, tiles, m_tiles, N, K, (char *)sink);
+    hipLaunchKernelGGL((grouped_gemm_nt<BM, BN, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes, st,
+                       (const __bf16 *)A, (__bf16 *)C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K,
+                       (char *)sink);
     return (int)hipGetLastError();
 }
 
 }  // namespace
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
-                     int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st)
+                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
-    return launch<true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, F, d, sink, st);
+    return launch<128, 128, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
-                     int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st)
+                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
-    return launch<false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles, d, F, sink, st);
+    return launch<128, 128, 2, 4, 4, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
+                                            m_tall, d, F, sink, st);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------

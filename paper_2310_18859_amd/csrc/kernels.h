@@ -30,12 +30,15 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
 // K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
-// tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles).
+// tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles); the
+// first m_tall of them belong to experts with more than kGemmTileM tokens.
 // sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
-                     const TileDesc *tiles, int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st);
+                     const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
+                     hipStream_t st);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
-                     const TileDesc *tiles, int32_t m_tiles, int32_t d, int32_t F, void *sink, hipStream_t st);
+                     const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
+                     hipStream_t st);
 // Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
