@@ -199,11 +199,13 @@ int prefetch_allowed(const sida_ctx *c, const sida_plan *p, int32_t w)
     return SIDA_OK;
 }
 
-int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, const Ws &ws, hipStream_t st)
+int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, const Ws &ws, const LayerTable *tbl,
+                    hipStream_t st)
 {
     {
         Timed tm(c, SIDA_K_SORT, st);
-        HIP_TRY(c, (hipError_t)launch_sort(ids, T, c->cfg.E, ws.counts, ws.offsets, ws.block_hist, ws.perm, ws.inv, st));
+        HIP_TRY(c, (hipError_t)launch_sort(ids, T, c->cfg.E, ws.counts, ws.offsets, ws.block_hist, ws.perm, ws.inv, tbl,
+                                           ws.tiles, ws.max_tiles, st));
     }
     {
         Timed tm(c, SIDA_K_GATHER, st);
@@ -295,11 +297,9 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
         const sida_plan *p = a.plan;
         if (p->n_waves == 0) continue;
         const Ws ws = carve(c->cfg, p->T, ws_dev);
-        rc = launch_dispatch(c, a.x, a.ids, p->T, ws, compute);
-        if (rc) return rc;
         LayerSchedule sched;
         build_schedule(p, &sched);
-        rc = launch_tiles(c, sched, ws, compute);
+        rc = launch_dispatch(c, a.x, a.ids, p->T, ws, &sched.tbl, compute);     // also expands sched.tbl into tiles
         if (rc) return rc;
         for (int32_t w = 0; w < p->n_waves; ++w) {
             const int32_t g = p->first_wave + w;
@@ -509,7 +509,7 @@ int sida_dispatch(sida_ctx *c, const void *x_dev, const int32_t *ids_dev, int32_
     if (!x_dev || !ids_dev) return SIDA_EINVAL;
     int rc = check_ws(c, T, workspace_dev, workspace_bytes);
     if (rc) return rc;
-    return launch_dispatch(c, x_dev, ids_dev, T, carve(c->cfg, T, workspace_dev), static_cast<hipStream_t>(stream));
+    return launch_dispatch(c, x_dev, ids_dev, T, carve(c->cfg, T, workspace_dev), nullptr, static_cast<hipStream_t>(stream));
 }
 
 int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *workspace_dev, size_t workspace_bytes,

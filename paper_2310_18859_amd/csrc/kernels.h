@@ -25,8 +25,10 @@ struct TileDesc {
 
 // K-a: stable counting sort of T tokens by expert id.
 //   ids int32[T] -> counts[E], offsets[E+1], perm[T], inv[T];  block_hist is scratch [n_chunks*E].
+// When tbl is given (may be NULL) it is also expanded into token tiles, see launch_build_tiles.
 int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32_t *offsets,
-                int32_t *block_hist, int32_t *perm, int32_t *inv, hipStream_t st);
+                int32_t *block_hist, int32_t *perm, int32_t *inv, const LayerTable *tbl, TileDesc *tiles,
+                int32_t max_tiles, hipStream_t st);
 // K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
