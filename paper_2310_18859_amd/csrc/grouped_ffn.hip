@@ -159,8 +159,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const int r = (wv * LOADS + j) * 8 + sub_row;     // row in the stage
-            src[j] = r < BM ? At + (size_t)(r % td.rows) * K * 2 + piece * 16    // rows past the end wrap around
-                            : Wt + (size_t)(r - BM) * K * 2 + piece * 16;        // (spread over all valid rows)
+            src[j] = r < BM ? At + (size_t)min(r, td.rows - 1) * K * 2 + piece * 16   // rows past the end re-read
+                            : Wt + (size_t)(r - BM) * K * 2 + piece * 16;             // the last one
         }
     };
     auto issue = [&]() {                                      // next stage of the stream
@@ -202,54 +202,43 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
 
     aim(ld_tile);
     int cp_row0 = ld_row0, cp_rows = ld_rows, cp_nt = ld_nt;  // tile the compute side works on
-    int nx_row0 = 0, nx_rows = 0, nx_nt = 0;
+    int nx_row0 = 0, nx_rows = 0, nx_nt = 0, nx2_row0 = 0, nx2_rows = 0, nx2_nt = 0;
     for (int s = 0; s < STAGES - 1 && s < steps; ++s) {
         issue();
         if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
     }
 
-    for (int step = 0; step < steps; ++step) {
-        // stages step .. step+STAGES-2 are in flight (fewer at the very end); stage `step` must have landed
-        // For the STAGES-1 steps after a tile's result stores those may be outstanding too (vector
-        // memory operations of a wavefront complete in issue order, stores included).
-        const int ahead = min(steps - 1 - step, STAGES - 2);
-        if (boost > 0 && ahead == STAGES - 2) wait_loads<(STAGES - 2) * LOADS + STORES>();
-        else wait_ahead<LOADS, STAGES - 2>(ahead);
-        if (boost > 0) --boost;
-        __builtin_amdgcn_s_barrier();                         // everyone's pieces of this stage are in LDS, and
-                                                              // everyone is done reading the stage refilled next
-        if (issued < steps) {
-            issue();
-            if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
-        }
-
+    // The two wavefronts that share a SIMD (w and w + NW/2) work half a step apart: between two
+    // barriers the "early" one reads its MFMA operands of the stage from LDS and then multiplies,
+    // the "late" one first multiplies what it read in the previous interval and then reads this
+    // stage.  So on every SIMD one wavefront's LDS reads overlap the other's MFMAs, while both have
+    // read a stage by the time the barrier that frees it is reached.
+    constexpr int KS = BK / 16;
+    const bool late = wv >= NW / 2;
+    bf16x8 xf[KS][MI], wf[KS][NI];
+    auto fetch = [&](int step) {
         const char *st = lds + (step % STAGES) * kStageBytes;
-        // MFMA operand fragments are fetched one K sub-step ahead of the MFMAs that use them, so
-        // the LDS latency is covered by matrix work
-        bf16x8 xf[2][MI], wf[2][NI];
-        auto fetch = [&](int ks, int into) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
             const int pos = ((ks * 2 + half) ^ sw) * 16;
 #pragma unroll
-            for (int i = 0; i < MI; ++i) xf[into][i] = *reinterpret_cast<const bf16x8 *>(st + x_off[i] + pos);
+            for (int i = 0; i < MI; ++i) xf[ks][i] = *reinterpret_cast<const bf16x8 *>(st + x_off[i] + pos);
 #pragma unroll
-            for (int i = 0; i < NI; ++i) wf[into][i] = *reinterpret_cast<const bf16x8 *>(st + w_off_l[i] + pos);
-        };
-        fetch(0, 0);
+            for (int i = 0; i < NI; ++i) wf[ks][i] = *reinterpret_cast<const bf16x8 *>(st + w_off_l[i] + pos);
+        }
+    };
+    auto multiply = [&]() {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int in = 0; in < NI; ++in)
 #pragma unroll
                 for (int im = 0; im < MI; ++im)
-                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][in], xf[ks & 1][im], acc[in][im],
-                                                                         0, 0, 0);
-        }
-
+                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][in], xf[ks][im], acc[in][im], 0, 0, 0);
         if (++cp_k == nk) {
             // ---- tile done: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4.
-            // Every thread issues all its stores (the wait above counts them): rows past the end of
-            // the tile go to a scratch sink instead of C.
+            // Every thread issues all its stores (the waits count them): rows past the end of the
+            // tile go to a scratch sink instead of C.
             if (!handover) {
                 int mt;
                 map_tile(cp_tile, m_tiles, m_tall, n_tiles_n, nw, &mt, &cp_nt);
@@ -277,12 +266,38 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                         *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
                     }
             }
-            if (handover) { cp_row0 = nx_row0; cp_rows = nx_rows; cp_nt = nx_nt; }
+            if (handover) { cp_row0 = nx2_row0; cp_rows = nx2_rows; cp_nt = nx2_nt; }
             boost = nk >= STAGES ? STAGES - 1 : 0;
             clear();
             cp_k = 0;
             cp_tile += G;
         }
+    };
+
+    // (the late wavefronts run one more interval, in which only their last multiplication is left)
+    for (int step = 0; step < steps + (late ? 1 : 0); ++step) {
+        const bool has_stage = step < steps;
+        if (has_stage) {
+            // stages step .. step+STAGES-2 are in flight (fewer at the very end); stage `step` must have
+            // landed.  For the STAGES-1 steps after a tile's result stores those may be outstanding too
+            // (vector memory operations of a wavefront complete in issue order, stores included).
+            const int ahead = min(steps - 1 - step, STAGES - 2);
+            if (boost > 0 && ahead == STAGES - 2) wait_loads<(STAGES - 2) * LOADS + STORES>();
+            else wait_ahead<LOADS, STAGES - 2>(ahead);
+            if (boost > 0) --boost;
+            __builtin_amdgcn_s_barrier();                     // everyone's pieces of this stage are in LDS, and
+                                                              // everyone is done reading the stage refilled next
+            // coordinates of the next tile for the compute side: the late wavefronts finish a tile one
+            // interval after the load side may have moved on, so they use a copy that is one interval old
+            nx2_row0 = nx_row0; nx2_rows = nx_rows; nx2_nt = nx_nt;
+            if (issued < steps) {
+                issue();
+                if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
+            }
+            if (!late) fetch(step);
+        }
+        if (!late || step > 0) multiply();                    // early: this stage; late: the previous one
+        if (late && has_stage) fetch(step);
     }
 }
 
@@ -328,6 +343,10 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
+    // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
+    // Switch shape, other widths fall back to 128
+    if (F % 256 == 0)
+        return launch<128, 256, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
     return launch<128, 128, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
 }
 
