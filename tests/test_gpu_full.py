@@ -1,0 +1,79 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(sida_run_layers over all layers, pool and wave sizes of the workload): integer results of every
+layer bit-exact against numpy's stable sort (which the oracle is pinned to), plans against the
+oracle's planner, and y on sampled tokens against the oracle (a token's output does not depend on
+the other tokens, so sampled rows can be computed one by one)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_close, bf16_tensor_to_f32, layer_inputs, make_runner, oracle_layer, say
+from workloads import WORKLOADS
+
+pytestmark = pytest.mark.gpu
+
+SAMPLES = 96     # tokens per layer checked against the oracle (plus every token of the smallest experts)
+
+
+def check_workload(wl, layers_checked):
+    say(f"full-size parity: {wl.name}  L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T} S={wl.S} W={wl.W}")
+    r = make_runner(wl)
+    say("  host weights ready")
+    st = oracle.PoolState(wl.E, wl.S)
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    worst = 0.0
+    for rep in range(2):                                  # second pass: the pool starts in its steady state
+        plans = r.plan_all([i[1] for i in ins])
+        dev = [r.to_device(*i) for i in ins]
+        r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
+        r.sync()
+        for l in range(wl.L):
+            x_bits, ids, alpha = ins[l]
+            op = st.plan_layer(l, ids, wl.W)
+            p = plans[l]
+            assert list(p.order)[:p.n_active] == op.order and list(p.slot)[:wl.E] == op.slot
+            assert list(p.wave)[:wl.E] == op.wave and list(p.hit)[:wl.E] == op.hit
+            assert list(p.wave_dep)[:p.n_waves] == op.wave_dep
+            if l not in layers_checked:
+                continue
+            y = bf16_tensor_to_f32(dev[l][3])
+            assert np.isfinite(y).all()
+            rng = np.random.default_rng(1000 * rep + l)
+            counts = np.bincount(ids, minlength=wl.E)
+            rare = np.argsort(counts)[:2]                 # the two least popular experts, all their tokens
+            rows = np.unique(np.concatenate([rng.choice(wl.T, SAMPLES, replace=False),
+                                             np.nonzero(np.isin(ids, rare))[0],
+                                             np.nonzero(ids == np.argmax(counts))[0][-40:],   # tail of the largest expert
+                                             [0, wl.T - 1]]))
+            ref = oracle_layer(wl, r, l, x_bits, ids, alpha, rows=rows)
+            worst = max(worst, assert_close(y[rows], ref, f"{wl.name} rep {rep} layer {l}"))
+        if rep == 0:                                      # the sort of the last layer is still in the workspace
+            l = wl.L - 1
+            ids = ins[l][1]
+            perm = np.argsort(ids, kind="stable").astype(np.int32)
+            inv = np.empty(wl.T, np.int32)
+            inv[perm] = np.arange(wl.T, dtype=np.int32)
+            assert np.array_equal(r.region(wl.T, "counts", torch.int32, (wl.E,)).cpu().numpy(), np.bincount(ids, minlength=wl.E))
+            assert np.array_equal(r.region(wl.T, "perm", torch.int32, (wl.T,)).cpu().numpy(), perm)
+            assert np.array_equal(r.region(wl.T, "inv", torch.int32, (wl.T,)).cpu().numpy(), inv)
+            xp = r.region(wl.T, "x_perm", torch.uint16, (wl.T, wl.d_model)).cpu().numpy()
+            assert np.array_equal(xp, ins[l][0][perm])
+        say(f"  pass {rep}: {sum(p.n_miss for p in plans)} expert loads, {sum(p.n_waves for p in plans)} waves, worst rel err so far {worst:.3e}")
+    r.close()
+
+
+def test_config1_switch_base_64():
+    check_workload(WORKLOADS[1], layers_checked=(0, 3, 5))
+
+
+def test_config2_switch_base_128():
+    check_workload(WORKLOADS[2], layers_checked=(0, 2, 5))
+
+
+def test_config3_switch_base_256():
+    check_workload(WORKLOADS[3], layers_checked=(0, 5))
+
+
+def test_config4_switch_large_128():
+    check_workload(WORKLOADS[4], layers_checked=(0, 11))
