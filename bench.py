@@ -25,9 +25,17 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 H2D_PEAK_GBS = 64.0            # PCIe Gen5 x16, one direction
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), see profiles/.
-# key: (workload name, mode, kernel) -> bytes per launch.  Empty until measured for that case.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch,
+# averaged over the launches of a run), scaled by what the same counters read for a plain 1 GiB
+# device copy (FETCH_SIZE reads half of the bytes actually fetched: factor 2.0; WRITE_SIZE: 1.0).
+# Source: profiles/grouped_ffn_switch-base-128.hbm_traffic.txt
+# key: (workload name, mode, kernel) -> bytes per launch (fetch + write).
+MEASURED_TRAFFIC = {
+    ("switch-base-128-T16384", "resident", "gemm1"): (379092.9 * 2.0 + 101620.5) * 1024,
+    ("switch-base-128-T16384", "resident", "gemm2"): (421903.3 * 2.0 + 25571.0) * 1024,
+    ("switch-base-128-T16384", "streaming", "gemm1"): (53944.6 * 2.0 + 12915.8) * 1024,
+    ("switch-base-128-T16384", "streaming", "gemm2"): (68643.6 * 2.0 + 3336.8) * 1024,
+}
 
 
 def log(*a):
@@ -98,17 +106,24 @@ def kernel_report(wl, prof, steps, n_miss_per_step):
 
 
 def cpu_baseline(wl, r, ins, budget_tokens):
+    """The oracle as it stands, timed on the host's cores over whole layers until the token budget is used."""
     import oracle
-    x_bits, ids, alpha = ins[0]
-    n = min(budget_tokens, wl.T)
     hw = r.host_weights.numpy()
-    blocks = [hw[e] for e in range(wl.E)]
+    done, layers = 0, 0
     t0 = time.perf_counter()
-    oracle.token_counts(ids[:n], wl.E)
-    oracle.moe_forward(x_bits[:n], ids[:n], alpha[:n], blocks, wl.d_model, wl.d_ff)
+    for l in range(wl.L):
+        if done >= budget_tokens:
+            break
+        x_bits, ids, alpha = ins[l]
+        n = min(budget_tokens - done, wl.T)
+        blocks = [hw[l * wl.E + e] for e in range(wl.E)]
+        oracle.token_counts(ids[:n], wl.E)
+        oracle.moe_forward(x_bits[:n], ids[:n], alpha[:n], blocks, wl.d_model, wl.d_ff)
+        done += n
+        layers += 1
     dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"first {n} tokens of layer 0 of {wl.name} (grouping + Eq. 1 per token), {dt:.1f} s"}
+    return {"value": done / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{done} tokens = the first {layers} layer(s) of {wl.name} (grouping + Eq. 1 per token), {dt:.1f} s"}
 
 
 def main():
@@ -120,8 +135,10 @@ def main():
     ap.add_argument("--resident-steps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with timing events")
-    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle sample (0 = pick for ~15 s)")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle sample (0 = four layers, ~10-15 s)")
     ap.add_argument("--only", choices=["both", "streaming", "resident"], default="both")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; 0 = as defined)")
     ap.add_argument("--zipf", type=float, default=None, help="override the Zipf exponent (0 = uniform ids)")
     a = ap.parse_args()
@@ -152,6 +169,15 @@ def main():
     dev = [r.to_device(*i) for i in ins]
     r.sync()
 
+    if a.calibrate_copy:                     # a plain copy kernel of known size: 1 GiB read, 1 GiB written
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(7)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     result = {}
     if a.only in ("both", "streaming"):
         r.ctx.profile_enable(not a.no_profile)
@@ -165,7 +191,7 @@ def main():
 
     cpu = None
     if not a.no_cpu_baseline:
-        n = a.cpu_tokens or wl.T
+        n = a.cpu_tokens or min(wl.L, 4) * wl.T
         log(f"[bench] timing the CPU oracle on {n} tokens ...")
         cpu = cpu_baseline(wl, r, ins, n)
         log(f"[bench] oracle: {cpu['value']:.1f} tokens/s on {cpu['cores']} threads")
