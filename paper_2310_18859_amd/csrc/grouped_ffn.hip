@@ -106,9 +106,13 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_t
     }
 }
 
-// Persistent workgroups: one per compute unit, each walks its tiles t = b, b+G, ... and treats
-// (tile, K-step) as ONE stream of stages.  The loads run STAGES-1 stages ahead of the MFMAs also
-// across tile boundaries, so the memory pipe does not drain between tiles.
+// Persistent workgroups: one per compute unit, each walks its tiles t = b, b+G, ...
+//
+// (tile, K-step) is ONE stream of stages: the loads run STAGES-1 stages ahead of the MFMAs, also
+// across tile boundaries.  The K loop of a tile is cut in two: while its first nk-(STAGES-1) steps
+// are multiplied the loads still fetch this tile, during the last STAGES-1 steps they already
+// fetch the next one.  Per step a wavefront executes: one s_waitcnt, one s_barrier, LOADS direct
+// loads with running pointers, the LDS fragment reads and the MFMAs - no tile bookkeeping.
 //
 // BM x BN is the output tile (tokens x weight rows), WM x WN the wavefront grid (8 wavefronts).
 template <int BM, int BN, int WM, int WN, int STAGES, bool RELU>
@@ -120,9 +124,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
 {
     constexpr int NW = WM * WN;
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
+    constexpr int kRingBytes = STAGES * kStageBytes;
     constexpr int LOADS = (BM + BN) / (8 * NW);               // direct loads per thread per K-step
     constexpr int MI = BM / (32 * WM);                        // 32-row MFMA blocks per wavefront along tokens
     constexpr int NI = BN / (32 * WN);                        //   ... along weight rows
+    constexpr int KS = BK / 16;                               // MFMA K sub-steps per stage
     constexpr int STORES = MI * NI * 4;                       // result stores per thread per tile
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM + BN) % (8 * NW) == 0 && BM % 8 == 0, "tile");
     static_assert(STAGES >= 2 && (STAGES - 2) * LOADS + STORES <= 63, "vmcnt range");
@@ -135,56 +141,58 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     const int total = m_tiles * n_tiles_n;
     const int G = gridDim.x;
     if ((int)blockIdx.x >= total) return;
-    const int my_tiles = (total - (int)blockIdx.x + G - 1) / G;
-    const int nk = K / BK;
-    const int steps = my_tiles * nk;
+    const int n = (total - (int)blockIdx.x + G - 1) / G;      // tiles of this workgroup
+    const int nk = K / BK;                                    // the launcher guarantees nk >= STAGES - 1
 
-    // ---- load side: lane i of a direct load covers row i/8 of its 8-row window, stored piece i%8 ----
+    // ---- load side.  A stage is BM token rows followed by BN weight rows, 128 bytes each; direct
+    // load number i of a stage fills rows 8i .. 8i+7 (1 KiB): lane l covers row l/8 of that window
+    // and stores at piece position l%8.  Wavefront w issues loads w*LOADS .. w*LOADS+LOADS-1.
     const int sub_row = lane >> 3;
     const int piece = (lane & 7) ^ sub_row;                   // logical 16-byte piece this lane fetches
-    // A stage is BM token rows followed by BN weight rows, 128 bytes each; direct load number i of
-    // a stage fills rows 8i .. 8i+7 (1 KiB); wavefront w issues loads w*LOADS .. w*LOADS+LOADS-1.
-    const char *src[LOADS];
-    int ld_tile = blockIdx.x, ld_k = 0, issued = 0;
-    int ld_row0 = 0, ld_rows = 0, ld_nt = 0;                  // tile the load side works on
-    auto aim = [&](int t) {                                   // point the load side at tile t
+    struct Coord {
+        int row0, rows, nt;
+    };
+    auto locate = [&](int i, Coord *c) {                      // i-th tile of this workgroup; returns its pool slot
         int mt, nt;
-        map_tile(t, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
+        map_tile((int)blockIdx.x + i * G, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
         const TileDesc td = tiles[mt];                        // uniform address: a scalar load
-        ld_row0 = td.row0;
-        ld_rows = td.rows;
-        ld_nt = nt;
-        const char *Wt = pool + (size_t)td.slot * expert_bytes + w_off + (size_t)nt * BN * K * 2;
-        const char *At = reinterpret_cast<const char *>(A) + (size_t)td.row0 * K * 2;
+        *c = Coord{td.row0, td.rows, nt};
+        return td.slot;
+    };
+    auto point = [&](const Coord &c, int slot, const char *(&p)[LOADS]) {
+        const char *Wt = pool + (size_t)slot * expert_bytes + w_off + (size_t)c.nt * BN * K * 2;
+        const char *At = reinterpret_cast<const char *>(A) + (size_t)c.row0 * K * 2;
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const int r = (wv * LOADS + j) * 8 + sub_row;     // row in the stage
-            src[j] = r < BM ? At + (size_t)min(r, td.rows - 1) * K * 2 + piece * 16   // rows past the end re-read
-                            : Wt + (size_t)(r - BM) * K * 2 + piece * 16;             // the last one
+            p[j] = r < BM ? At + (size_t)min(r, c.rows - 1) * K * 2 + piece * 16    // rows past the end re-read
+                          : Wt + (size_t)(r - BM) * K * 2 + piece * 16;              // the last one
         }
     };
-    auto issue = [&]() {                                      // next stage of the stream
-        char *dst = lds + (issued % STAGES) * kStageBytes + wv * LOADS * 1024;
-        const size_t koff = (size_t)ld_k * kRowBytes;
+    int wr_off = 0;                                           // ring offset of the stage filled next
+    auto issue = [&](const char *(&p)[LOADS]) {               // next K-step of the tile p points into
+        char *dst = lds + wr_off + wv * LOADS * 1024;
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) load_to_lds(src[j] + koff, dst + j * 1024);
-        ++issued;
-        if (++ld_k == nk) {
-            ld_k = 0;
-            ld_tile += G;
-            if (issued < steps) aim(ld_tile);
+        for (int j = 0; j < LOADS; ++j) {
+            load_to_lds(p[j], dst + j * 1024);
+            p[j] += kRowBytes;
         }
+        wr_off = wr_off + kStageBytes == kRingBytes ? 0 : wr_off + kStageBytes;
     };
 
     // ---- compute side ----
     const int wm = wv % WM, wn = wv / WM;                     // wavefront position in the WM x WN grid
     const int frag_row = lane & 31, half = lane >> 5;
     const int sw = frag_row & 7;
-    int x_off[MI], w_off_l[NI];
+    int x_at[MI][KS], w_at[NI][KS];                           // fragment offsets inside a stage
 #pragma unroll
-    for (int i = 0; i < MI; ++i) x_off[i] = (wm * (BM / WM) + i * 32 + frag_row) * kRowBytes;
+    for (int ks = 0; ks < KS; ++ks) {
+        const int pos = ((ks * 2 + half) ^ sw) * 16;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) w_off_l[i] = BM * kRowBytes + (wn * (BN / WN) + i * 32 + frag_row) * kRowBytes;
+        for (int i = 0; i < MI; ++i) x_at[i][ks] = (wm * (BM / WM) + i * 32 + frag_row) * kRowBytes + pos;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) w_at[i][ks] = BM * kRowBytes + (wn * (BN / WN) + i * 32 + frag_row) * kRowBytes + pos;
+    }
     f32x16 acc[NI][MI];
     auto clear = [&]() {
 #pragma unroll
@@ -194,110 +202,95 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     };
-    clear();
-    // The loads are at most one tile ahead of the MFMAs when a tile has at least STAGES-1 K-steps;
-    // then the compute side can take each tile's coordinates over from the load side.
-    const bool handover = nk >= STAGES - 1;
-    int cp_tile = blockIdx.x, cp_k = 0, boost = 0;
-
-    aim(ld_tile);
-    int cp_row0 = ld_row0, cp_rows = ld_rows, cp_nt = ld_nt;  // tile the compute side works on
-    int nx_row0 = 0, nx_rows = 0, nx_nt = 0, nx2_row0 = 0, nx2_rows = 0, nx2_nt = 0;
-    for (int s = 0; s < STAGES - 1 && s < steps; ++s) {
-        issue();
-        if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
-    }
-
-    // The two wavefronts that share a SIMD (w and w + NW/2) work half a step apart: between two
-    // barriers the "early" one reads its MFMA operands of the stage from LDS and then multiplies,
-    // the "late" one first multiplies what it read in the previous interval and then reads this
-    // stage.  So on every SIMD one wavefront's LDS reads overlap the other's MFMAs, while both have
-    // read a stage by the time the barrier that frees it is reached.
-    constexpr int KS = BK / 16;
-    const bool late = wv >= NW / 2;
-    bf16x8 xf[KS][MI], wf[KS][NI];
-    auto fetch = [&](int step) {
-        const char *st = lds + (step % STAGES) * kStageBytes;
+    int rd_off = 0;                                           // ring offset of the stage multiplied next
+    auto multiply_stage = [&]() {
+        const char *st = lds + rd_off;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const int pos = ((ks * 2 + half) ^ sw) * 16;
+            bf16x8 xf[MI], wf[NI];
 #pragma unroll
-            for (int i = 0; i < MI; ++i) xf[ks][i] = *reinterpret_cast<const bf16x8 *>(st + x_off[i] + pos);
+            for (int i = 0; i < MI; ++i) xf[i] = *reinterpret_cast<const bf16x8 *>(st + x_at[i][ks]);
 #pragma unroll
-            for (int i = 0; i < NI; ++i) wf[ks][i] = *reinterpret_cast<const bf16x8 *>(st + w_off_l[i] + pos);
-        }
-    };
-    auto multiply = [&]() {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+            for (int i = 0; i < NI; ++i) wf[i] = *reinterpret_cast<const bf16x8 *>(st + w_at[i][ks]);
 #pragma unroll
             for (int in = 0; in < NI; ++in)
 #pragma unroll
                 for (int im = 0; im < MI; ++im)
-                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][in], xf[ks][im], acc[in][im], 0, 0, 0);
-        if (++cp_k == nk) {
-            // ---- tile done: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4.
-            // Every thread issues all its stores (the waits count them): rows past the end of the
-            // tile go to a scratch sink instead of C.
-            if (!handover) {
-                int mt;
-                map_tile(cp_tile, m_tiles, m_tall, n_tiles_n, nw, &mt, &cp_nt);
-                const TileDesc td = tiles[mt];
-                cp_row0 = td.row0;
-                cp_rows = td.rows;
-            }
+                    acc[in][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[in], xf[im], acc[in][im], 0, 0, 0);
+        }
+        rd_off = rd_off + kStageBytes == kRingBytes ? 0 : rd_off + kStageBytes;
+    };
+    // Result stores: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4.  Every
+    // thread issues all its stores (the waits count them): rows past the end of the tile go to a
+    // scratch sink instead of C.
+    auto store_tile = [&](const Coord &c) {
 #pragma unroll
-            for (int im = 0; im < MI; ++im) {
-                const int m = wm * (BM / WM) + im * 32 + frag_row;
-                __bf16 *crow = m < cp_rows
-                                   ? C + (size_t)(cp_row0 + m) * N + (size_t)cp_nt * BN + wn * (BN / WN)
-                                   : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * (NI * 32);
+        for (int im = 0; im < MI; ++im) {
+            const int m = wm * (BM / WM) + im * 32 + frag_row;
+            __bf16 *crow = m < c.rows ? C + (size_t)(c.row0 + m) * N + (size_t)c.nt * BN + wn * (BN / WN)
+                                      : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * (NI * 32);
 #pragma unroll
-                for (int in = 0; in < NI; ++in)
+            for (int in = 0; in < NI; ++in)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        bf16x4 o;
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 o;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            float v = acc[in][im][q * 4 + j];
-                            if (RELU) v = v > 0.f ? v : 0.f;
-                            o[j] = (__bf16)v;
-                        }
-                        *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
+                    for (int j = 0; j < 4; ++j) {
+                        float v = acc[in][im][q * 4 + j];
+                        if (RELU) v = v > 0.f ? v : 0.f;
+                        o[j] = (__bf16)v;
                     }
-            }
-            if (handover) { cp_row0 = nx2_row0; cp_rows = nx2_rows; cp_nt = nx2_nt; }
-            boost = nk >= STAGES ? STAGES - 1 : 0;
-            clear();
-            cp_k = 0;
-            cp_tile += G;
+                    *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
+                }
         }
     };
 
-    // (the late wavefronts run one more interval, in which only their last multiplication is left)
-    for (int step = 0; step < steps + (late ? 1 : 0); ++step) {
-        const bool has_stage = step < steps;
-        if (has_stage) {
-            // stages step .. step+STAGES-2 are in flight (fewer at the very end); stage `step` must have
-            // landed.  For the STAGES-1 steps after a tile's result stores those may be outstanding too
-            // (vector memory operations of a wavefront complete in issue order, stores included).
-            const int ahead = min(steps - 1 - step, STAGES - 2);
-            if (boost > 0 && ahead == STAGES - 2) wait_loads<(STAGES - 2) * LOADS + STORES>();
-            else wait_ahead<LOADS, STAGES - 2>(ahead);
-            if (boost > 0) --boost;
+    const char *cur[LOADS];                                   // running load pointers
+    Coord cc, nc;
+    int slot = locate(0, &cc);
+    nc = cc;
+    point(cc, slot, cur);
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(cur);          // K-steps 0 .. STAGES-2 of the first tile
+    clear();
+
+    for (int t = 0; t < n; ++t) {
+        const bool has_next = t + 1 < n;
+        int next_slot = 0;
+        if (has_next) next_slot = locate(t + 1, &nc);         // used only after the first part of the K loop
+        // ---- K-steps whose loads still belong to this tile.  For the first STAGES-1 steps after a
+        // tile's result stores those may be outstanding too (vector memory operations of a
+        // wavefront complete in issue order, stores included).
+        for (int k = 0; k <= nk - STAGES; ++k) {
+            if (t > 0 && k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES>();
+            else wait_loads<(STAGES - 2) * LOADS>();
             __builtin_amdgcn_s_barrier();                     // everyone's pieces of this stage are in LDS, and
                                                               // everyone is done reading the stage refilled next
-            // coordinates of the next tile for the compute side: the late wavefronts finish a tile one
-            // interval after the load side may have moved on, so they use a copy that is one interval old
-            nx2_row0 = nx_row0; nx2_rows = nx_rows; nx2_nt = nx_nt;
-            if (issued < steps) {
-                issue();
-                if (ld_k == 0) { nx_row0 = ld_row0; nx_rows = ld_rows; nx_nt = ld_nt; }
-            }
-            if (!late) fetch(step);
+            issue(cur);
+            multiply_stage();
         }
-        if (!late || step > 0) multiply();                    // early: this stage; late: the previous one
-        if (late && has_stage) fetch(step);
+        // ---- last STAGES-1 K-steps: the loads already fetch the next tile
+        if (has_next) {
+            point(nc, next_slot, cur);                        // all loads of this tile have been issued
+#pragma unroll
+            for (int k = 0; k < STAGES - 1; ++k) {
+                if (t > 0 && nk - (STAGES - 1) + k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES>();
+                else wait_loads<(STAGES - 2) * LOADS>();
+                __builtin_amdgcn_s_barrier();
+                issue(cur);
+                multiply_stage();
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < STAGES - 1; ++k) {            // the stream ends: nothing more to fetch
+                wait_loads<0>();
+                __builtin_amdgcn_s_barrier();
+                multiply_stage();
+            }
+        }
+        store_tile(cc);
+        clear();
+        cc = nc;
     }
 }
 
@@ -347,12 +340,17 @@ int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t exper
     // Switch shape, other widths fall back to 128
     if (F % 256 == 0)
         return launch<128, 256, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+    if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
+        return launch<128, 128, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
     return launch<128, 128, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
+    if (F < 192)
+        return launch<128, 128, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
+                                                m_tall, d, F, sink, st);
     return launch<128, 128, 2, 4, 4, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
                                             m_tall, d, F, sink, st);
 }
