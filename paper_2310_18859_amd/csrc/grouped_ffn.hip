@@ -38,8 +38,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BK = 64;           // K step
-constexpr int kRowBytes = BK * 2;
 
 template <int N>
 __device__ __forceinline__ void wait_loads()
@@ -115,7 +113,7 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_t
 // loads with running pointers, the LDS fragment reads and the MFMAs - no tile bookkeeping.
 //
 // BM x BN is the output tile (tokens x weight rows), WM x WN the wavefront grid (8 wavefronts).
-template <int BM, int BN, int WM, int WN, int STAGES, bool RELU>
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
 __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
                                                                const char *__restrict__ pool, size_t expert_bytes,
                                                                size_t w_off, const TileDesc *__restrict__ tiles,
@@ -123,16 +121,20 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                                                                char *__restrict__ sink)
 {
     constexpr int NW = WM * WN;
+    constexpr int kRowBytes = BK * 2;                         // a tile row in LDS: BK bf16 (128 or 64 bytes)
+    constexpr int PPR = kRowBytes / 16;                       // 16-byte pieces per row
+    constexpr int RPL = 64 / PPR;                             // rows filled by one direct load (1 KiB)
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     constexpr int kRingBytes = STAGES * kStageBytes;
-    constexpr int LOADS = (BM + BN) / (8 * NW);               // direct loads per thread per K-step
+    constexpr int LOADS = (BM + BN) / (RPL * NW);             // direct loads per thread per K-step
+    static_assert(BK == 64 || BK == 32, "K step");
     constexpr int MI = BM / (32 * WM);                        // 32-row MFMA blocks per wavefront along tokens
     constexpr int NI = BN / (32 * WN);                        //   ... along weight rows
     constexpr int KS = BK / 16;                               // MFMA K sub-steps per stage
-    constexpr int STORES = MI * NI * 4;                       // result stores per thread per tile
-    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM + BN) % (8 * NW) == 0 && BM % 8 == 0, "tile");
+    constexpr int STORES = MI * NI * 2;                       // result stores per thread per tile (16 bytes each)
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM + BN) % (RPL * NW) == 0 && BM % RPL == 0, "tile");
     static_assert(STAGES >= 2 && (STAGES - 2) * LOADS + STORES <= 63, "vmcnt range");
-    static_assert(NW * 64 * NI * 64 <= kGemmSinkBytes, "sink size");
+    static_assert(NW * 64 * 16 <= kGemmSinkBytes, "sink size");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -144,11 +146,13 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     const int n = (total - (int)blockIdx.x + G - 1) / G;      // tiles of this workgroup
     const int nk = K / BK;                                    // the launcher guarantees nk >= STAGES - 1
 
-    // ---- load side.  A stage is BM token rows followed by BN weight rows, 128 bytes each; direct
-    // load number i of a stage fills rows 8i .. 8i+7 (1 KiB): lane l covers row l/8 of that window
-    // and stores at piece position l%8.  Wavefront w issues loads w*LOADS .. w*LOADS+LOADS-1.
-    const int sub_row = lane >> 3;
-    const int piece = (lane & 7) ^ sub_row;                   // logical 16-byte piece this lane fetches
+    // ---- load side.  A stage is BM token rows followed by BN weight rows; direct load number i of
+    // a stage fills rows RPL*i .. RPL*i+RPL-1 (1 KiB): lane l covers row l/PPR of that window and
+    // stores at piece position l%PPR.  Swizzle: piece c of row r is stored at position c ^ (r & 7)
+    // for 128-byte rows and at c ^ ((r >> 2) & 3) for 64-byte rows; both make the 32-row fragment
+    // reads conflict free.  Wavefront w issues loads w*LOADS .. w*LOADS+LOADS-1 of every stage.
+    const int sub_row = lane / PPR;
+    const int piece = (lane % PPR) ^ (BK == 64 ? sub_row : (sub_row >> 2) & 3);   // logical piece this lane fetches
     struct Coord {
         int row0, rows, nt;
     };
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         const char *At = reinterpret_cast<const char *>(A) + (size_t)c.row0 * K * 2;
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
-            const int r = (wv * LOADS + j) * 8 + sub_row;     // row in the stage
+            const int r = (wv * LOADS + j) * RPL + sub_row;   // row in the stage
             p[j] = r < BM ? At + (size_t)min(r, c.rows - 1) * K * 2 + piece * 16    // rows past the end re-read
                           : Wt + (size_t)(r - BM) * K * 2 + piece * 16;              // the last one
         }
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     // ---- compute side ----
     const int wm = wv % WM, wn = wv / WM;                     // wavefront position in the WM x WN grid
     const int frag_row = lane & 31, half = lane >> 5;
-    const int sw = frag_row & 7;
+    const int sw = BK == 64 ? (frag_row & 7) : ((frag_row >> 2) & 3);
     int x_at[MI][KS], w_at[NI][KS];                           // fragment offsets inside a stage
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -220,15 +224,24 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         }
         rd_off = rd_off + kStageBytes == kRingBytes ? 0 : rd_off + kStageBytes;
     };
-    // Result stores: lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4.  Every
-    // thread issues all its stores (the waits count them): rows past the end of the tile go to a
-    // scratch sink instead of C.
+    // Result stores.  A lane holds D[n][m] with m = lane&31 and n = 8*(r/4) + 4*(lane>>5) + r%4, i.e.
+    // 8-byte runs of 32 different token rows.  Each wavefront turns its 32-row blocks around through
+    // a private piece of the stage that was multiplied last (free until the next K-step refills it)
+    // and then stores 16 bytes per lane, consecutive lanes covering whole output-row segments.
+    // Every thread issues all its stores (the waits count them): rows past the end of the tile go
+    // to a scratch sink instead of C.
+    constexpr int kOutCols = NI * 32;                         // output columns of a wavefront
+    constexpr int kOutPitch = kOutCols * 2 + 16;              // staging row pitch in bytes
+    constexpr int LPR = kOutCols * 2 / 16;                    // lanes per output-row segment
+    constexpr int RPI = 64 / LPR;                             // rows per store instruction
+    static_assert(STORES == MI * (32 / RPI), "store count");
+    static_assert(NW * 32 * kOutPitch <= kStageBytes, "staging fits in a stage");
     auto store_tile = [&](const Coord &c) {
+        __builtin_amdgcn_s_barrier();                         // everyone is done reading the last stage
+        char *stg = lds + (rd_off == 0 ? kRingBytes - kStageBytes : rd_off - kStageBytes) + wv * (32 * kOutPitch);
+        const int seg = lane % LPR, srow = lane / LPR;
 #pragma unroll
         for (int im = 0; im < MI; ++im) {
-            const int m = wm * (BM / WM) + im * 32 + frag_row;
-            __bf16 *crow = m < c.rows ? C + (size_t)(c.row0 + m) * N + (size_t)c.nt * BN + wn * (BN / WN)
-                                      : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * (NI * 32);
 #pragma unroll
             for (int in = 0; in < NI; ++in)
 #pragma unroll
@@ -240,8 +253,18 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                         if (RELU) v = v > 0.f ? v : 0.f;
                         o[j] = (__bf16)v;
                     }
-                    *reinterpret_cast<bf16x4 *>(crow + in * 32 + q * 8 + half * 4) = o;
+                    *reinterpret_cast<bf16x4 *>(stg + frag_row * kOutPitch + (in * 32 + q * 8 + half * 4) * 2) = o;
                 }
+            // LDS operations of one wavefront execute in order: no barrier between its writes and reads
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int r = i * RPI + srow;
+                const int m = wm * (BM / WM) + im * 32 + r;
+                const bf16x8 v = *reinterpret_cast<const bf16x8 *>(stg + r * kOutPitch + seg * 16);
+                __bf16 *dst = m < c.rows ? C + (size_t)(c.row0 + m) * N + (size_t)c.nt * BN + wn * (BN / WN) + seg * 8
+                                         : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * 8;
+                *reinterpret_cast<bf16x8 *>(dst) = v;
+            }
         }
     };
 
@@ -306,15 +329,23 @@ int persistent_grid()
     return cus;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool RELU>
+#ifndef KB1
+#define KB1 64
+#define ST1 3
+#endif
+#ifndef KB2
+#define KB2 64
+#define ST2 4
+#endif
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
 int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
            int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, hipStream_t st)
 {
-    constexpr int kLdsBytes = STAGES * (BM + BN) * kRowBytes;
+    constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2;
     static_assert(kLdsBytes <= 160 * 1024, "LDS");
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, BN, WM, WN, STAGES, RELU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
@@ -325,7 +356,7 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
     while (n_tiles_n % nw) --nw;
     const int total = m_tiles * n_tiles_n;
     const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
-    hipLaunchKernelGGL((grouped_gemm_nt<BM, BN, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes, st,
+    hipLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes, st,
                        (const __bf16 *)A, (__bf16 *)C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K,
                        (char *)sink);
     return (int)hipGetLastError();
@@ -338,20 +369,22 @@ int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t exper
 {
     // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
     // Switch shape, other widths fall back to 128
-    if (F % 256 == 0)
-        return launch<128, 256, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+    if (F % 256 == 0 && d >= KB1 * (ST1 - 1))
+        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+    if (F % 256 == 0 && d >= 128)
+        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
     if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
-        return launch<128, 128, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
-    return launch<128, 128, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
 {
-    if (F < 192)
-        return launch<128, 128, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
+    if (F < KB2 * (ST2 - 1))
+        return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
                                                 m_tall, d, F, sink, st);
-    return launch<128, 128, 2, 4, 4, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
+    return launch<128, 128, KB2, 2, 4, ST2, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
                                             m_tall, d, F, sink, st);
 }
 
