@@ -123,6 +123,28 @@ struct Timed {
     }
 };
 
+// Timing record of a class that is one kernel: the events ride on the kernel's own dispatch.
+struct TimedKernel {
+    LaunchEvents ev{};
+    bool on = false;
+    TimedKernel(sida_ctx *c, int klass)
+    {
+        if (!c->profiling) return;
+        if (c->prof_used == c->prof_pool.size()) {
+            if (c->prof_pool.size() >= (size_t)kProfRing) return;
+            ProfRec r{};
+            if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+            c->prof_pool.push_back(r);
+        }
+        ProfRec *rec = &c->prof_pool[c->prof_used++];
+        rec->klass = klass;
+        ev.start = rec->start;
+        ev.stop = rec->stop;
+        on = true;
+    }
+    const LaunchEvents *get() const { return on ? &ev : nullptr; }
+};
+
 // Tile schedule of a layer: the activated experts wave by wave, inside a wave most tokens first,
 // and for every local wave the range of token tiles it owns in the expanded descriptor array.
 struct LayerSchedule {
@@ -208,8 +230,8 @@ int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, c
                                            ws.tiles, ws.max_tiles, st));
     }
     {
-        Timed tm(c, SIDA_K_GATHER, st);
-        HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st));
+        TimedKernel tk(c, SIDA_K_GATHER);
+        HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st, tk.get()));
     }
     return SIDA_OK;
 }
@@ -225,14 +247,14 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
 {
     const TileDesc *tiles = ws.tiles + s.tile_begin[w];
     {
-        Timed tm(c, SIDA_K_GEMM1, st);
+        TimedKernel tk(c, SIDA_K_GEMM1);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get()));
     }
     {
-        Timed tm(c, SIDA_K_GEMM2, st);
+        TimedKernel tk(c, SIDA_K_GEMM2);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st));
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get()));
     }
     return SIDA_OK;
 }
@@ -320,8 +342,8 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
             c->forwarded_upto = g + 1;
         }
         {
-            Timed tm(c, SIDA_K_COMBINE, compute);
-            HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute));
+            TimedKernel tk(c, SIDA_K_COMBINE);
+            HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute, tk.get()));
         }
     }
     return SIDA_OK;
@@ -539,8 +561,8 @@ int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, vo
     if (rc) return rc;
     const Ws ws = carve(c->cfg, T, workspace_dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Timed tm(c, SIDA_K_COMBINE, st);
-    HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st));
+    TimedKernel tk(c, SIDA_K_COMBINE);
+    HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st, tk.get()));
     return SIDA_OK;
 }
 

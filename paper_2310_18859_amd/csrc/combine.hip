@@ -2,6 +2,7 @@
 // the expert outputs go back from expert order to token order:
 //     y[t,:] = alpha[t] * y_perm[inv[t],:]
 // The product is taken in fp32 and rounded to bf16 once (round to nearest even).
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -36,10 +37,10 @@ __global__ __launch_bounds__(256) void combine_rows(const bf16x8 *__restrict__ y
 }  // namespace
 
 int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, int32_t T, int32_t d,
-                   void *y, hipStream_t st)
+                   void *y, hipStream_t st, const LaunchEvents *ev)
 {
-    hipLaunchKernelGGL(combine_rows, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16x8 *)y_perm, inv,
-                       alpha, T, d / 8, (bf16x8 *)y);
+    hipExtLaunchKernelGGL(combine_rows, dim3((T + 3) / 4), dim3(256), 0, st, ev ? ev->start : nullptr,
+                          ev ? ev->stop : nullptr, 0, (const bf16x8 *)y_perm, inv, alpha, T, d / 8, (bf16x8 *)y);
     return (int)hipGetLastError();
 }
 

@@ -26,6 +26,7 @@
 // the instruction's 1 KB window (8 rows), so lane i fetches global piece (i%8) ^ (i/8) of row i/8;
 // the MFMA fragment reads (32 rows, same logical piece) then touch 8 different positions per
 // 8 rows and are bank-conflict free without padding.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -329,6 +330,9 @@ int persistent_grid()
     return cus;
 }
 
+// K step and ring depth of the two main shapes.  Measured on the Switch-base-128 workload: a K
+// step of 32 with a deeper ring (more bytes in flight, 64-byte row segments) is slower, and a
+// fifth stage for the 128 x 128 shape changes nothing.
 #ifndef KB1
 #define KB1 64
 #define ST1 3
@@ -339,7 +343,7 @@ int persistent_grid()
 #endif
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
 int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
-           int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, hipStream_t st)
+           int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, hipStream_t st, const LaunchEvents *ev)
 {
     constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2;
     static_assert(kLdsBytes <= 160 * 1024, "LDS");
@@ -350,42 +354,50 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    if (m_tiles <= 0) return 0;
+    if (m_tiles <= 0) {                                      // nothing to launch: keep the events usable
+        if (ev) {
+            (void)hipEventRecord(ev->start, st);
+            (void)hipEventRecord(ev->stop, st);
+        }
+        return 0;
+    }
     const int n_tiles_n = N / BN;
     int nw = n_tiles_n < 8 ? n_tiles_n : 8;                  // weight-row tiles per block of a many-token group
     while (n_tiles_n % nw) --nw;
     const int total = m_tiles * n_tiles_n;
     const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
-    hipLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes, st,
-                       (const __bf16 *)A, (__bf16 *)C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K,
-                       (char *)sink);
+    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes,
+                          st, ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, (const __bf16 *)A, (__bf16 *)C, pool,
+                          expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink);
     return (int)hipGetLastError();
 }
 
 }  // namespace
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
-                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
+                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
+                     const LaunchEvents *ev)
 {
     // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
     // Switch shape, other widths fall back to 128
     if (F % 256 == 0 && d >= KB1 * (ST1 - 1))
-        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
     if (F % 256 == 0 && d >= 128)
-        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
     if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
-        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
-    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st);
+        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
+    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
-                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st)
+                     int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
+                     const LaunchEvents *ev)
 {
     if (F < KB2 * (ST2 - 1))
         return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                                m_tall, d, F, sink, st);
+                                                m_tall, d, F, sink, st, ev);
     return launch<128, 128, KB2, 2, 4, ST2, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                            m_tall, d, F, sink, st);
+                                            m_tall, d, F, sink, st, ev);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------

@@ -23,6 +23,13 @@ struct TileDesc {
     int32_t expert;
 };
 
+// Optional timing of a single-kernel launch: the two events are attached to the kernel's own
+// dispatch, so their elapsed time is the kernel's execution time without the gaps a pair of
+// hipEventRecord calls around the launch would add.  NULL = not timed.
+struct LaunchEvents {
+    hipEvent_t start, stop;
+};
+
 // K-a: stable counting sort of T tokens by expert id.
 //   ids int32[T] -> counts[E], offsets[E+1], perm[T], inv[T];  block_hist is scratch [n_chunks*E].
 // When tbl is given (may be NULL) it is also expanded into token tiles, see launch_build_tiles.
@@ -30,24 +37,25 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
                 int32_t *block_hist, int32_t *perm, int32_t *inv, const LayerTable *tbl, TileDesc *tiles,
                 int32_t max_tiles, hipStream_t st);
 // K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
-int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st);
+int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st,
+                  const LaunchEvents *ev = nullptr);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
 // tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles); the
 // first m_tall of them belong to experts with more than kGemmTileM tokens.
 // sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st);
+                     hipStream_t st, const LaunchEvents *ev = nullptr);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st);
+                     hipStream_t st, const LaunchEvents *ev = nullptr);
 // Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
                        hipStream_t st);
 // K-c: y[t,:] = alpha[t] * y_perm[inv[t],:].
 int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, int32_t T, int32_t d,
-                   void *y, hipStream_t st);
+                   void *y, hipStream_t st, const LaunchEvents *ev = nullptr);
 
 constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)

@@ -14,6 +14,7 @@
 //               earlier chunks) + (earlier rounds of this chunk) + (lower lanes of this round, by
 //               wavefront ballots over the 8 id bits)
 //   gather_rows one wavefront per output row, 16-byte accesses
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -214,11 +215,12 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
     return (int)hipGetLastError();
 }
 
-int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st)
+int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st,
+                  const LaunchEvents *ev)
 {
     const int vec_per_row = d / 8;
-    hipLaunchKernelGGL(gather_rows, dim3((T + 3) / 4), dim3(256), 0, st, (const uint4 *)x, perm, T,
-                       vec_per_row, (uint4 *)x_perm);
+    hipExtLaunchKernelGGL(gather_rows, dim3((T + 3) / 4), dim3(256), 0, st, ev ? ev->start : nullptr,
+                          ev ? ev->stop : nullptr, 0, (const uint4 *)x, perm, T, vec_per_row, (uint4 *)x_perm);
     return (int)hipGetLastError();
 }
 
