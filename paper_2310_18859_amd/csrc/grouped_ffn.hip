@@ -15,15 +15,16 @@
 // ahead of the MFMAs, with one workgroup barrier per K-step.
 //
 // Tiling: one workgroup of WM x WN wavefronts computes a BM (tokens) x BN (weight rows) tile, K in
-// steps of 64; each wavefront owns (BM/WM) x (BN/WN) as MFMA 32x32x16 tiles, fp32 accumulators.
+// steps of BK; each wavefront owns (BM/WM) x (BN/WN) as MFMA 32x32x16 tiles, fp32 accumulators.
 // Eight wavefronts per compute unit are needed to pull enough bytes per clock out of L2 with
 // direct-to-LDS loads (four reach about half of that).  The weight rows are the MFMA's first
 // operand and the token rows the second, so a lane ends up with 4 consecutive output columns of
-// one token row and stores them as one 8-byte piece.
+// one token row; finished tiles are turned around through LDS so that the global stores are
+// 16 bytes per lane and consecutive lanes cover whole row segments.
 //
-// LDS tile layout: row r of a tile is 128 bytes (64 bf16); its 16-byte piece c is stored at
-// piece position c ^ (r & 7).  A direct-to-LDS load writes lane i's 16 bytes at offset 16*i of
-// the instruction's 1 KB window (8 rows), so lane i fetches global piece (i%8) ^ (i/8) of row i/8;
+// LDS tile layout (BK = 64): row r of a tile is 128 bytes; its 16-byte piece c is stored at piece
+// position c ^ (r & 7).  A direct-to-LDS load writes lane i's 16 bytes at offset 16*i of the
+// instruction's 1 KB window (8 rows), so lane i fetches global piece (i%8) ^ (i/8) of row i/8;
 // the MFMA fragment reads (32 rows, same logical piece) then touch 8 different positions per
 // 8 rows and are bank-conflict free without padding.
 #include <hip/hip_ext.h>
@@ -50,18 +51,6 @@ __device__ __forceinline__ void load_to_lds(const void *gsrc, void *lds_dst)
 {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
                                      (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
-}
-
-// Waits until at most ahead*LOADS of this thread's direct loads are outstanding (ahead <= MAXA).
-template <int LOADS, int MAXA>
-__device__ __forceinline__ void wait_ahead(int ahead)
-{
-    if constexpr (MAXA == 0) {
-        wait_loads<0>();
-    } else {
-        if (ahead >= MAXA) wait_loads<MAXA * LOADS>();
-        else wait_ahead<LOADS, MAXA - 1>(ahead);
-    }
 }
 
 // Output tile t of a launch -> (token tile, weight-row tile).
