@@ -17,8 +17,17 @@ scaling factor looked up per token as in Section 3.1).  Integer parts, all plain
   age; the budget is global over layers (key = layer*E + e); when more experts are needed by
   one layer than fit, the layer is cut into waves of at most W experts, and a slot may only be
   overwritten after the wave that last computed from it has finished (``wave_dep``).
+* Replacement policies other than first-in-first-out (the footnote of Section 4.3 allows them):
+  ``"lru"`` overwrites the expert that was loaded or hit longest ago, ``"belady"`` the expert
+  whose next use lies farthest ahead in the known future - the rest of the current layer, then
+  ``future_keys``, which the hash-table queue of Section 3.1 makes available (ties: the oldest
+  load).  Both use empty slots first and never take a slot of the wave being assembled.
+* ``serve_plans``: the inference thread's loop over a queue of hash tables (Algorithm 1,
+  Section 3.1): batches are planned in arrival order, layer by layer, each layer seeing the
+  later layers of its batch and the queued batches behind it as its future.
 
-Pins: tests/test_oracle_forward.py, tests/test_oracle_sort.py, tests/test_oracle_plan.py.
+Pins: tests/test_oracle_forward.py, tests/test_oracle_sort.py, tests/test_oracle_plan.py,
+tests/test_oracle_policies.py.
 """
 from __future__ import annotations
 
@@ -151,19 +160,57 @@ class LayerPlan:
         return len(self.order)
 
 
-class PoolState:
-    """S equal-sized expert slots, shared by all layers, replaced first-in-first-out."""
+NEVER = 1 << 60     # "not used again" as a next-use distance
 
-    def __init__(self, E: int, S: int):
+
+def first_appearance(ids, E: int):
+    """Experts of a layer in the order Algorithm 1 meets them when it walks the tokens."""
+    seen, order = [False] * E, []
+    for k in ids:
+        k = int(k)
+        if not 0 <= k < E:
+            raise ValueError("expert id out of range")
+        if not seen[k]:
+            seen[k] = True
+            order.append(k)
+    return order
+
+
+class PoolState:
+    """S equal-sized expert slots, shared by all layers.  policy: "fifo" (the paper's), "lru", "belady"."""
+
+    def __init__(self, E: int, S: int, policy: str = "fifo"):
         if S < 1 or E < 1:
             raise ValueError("need S >= 1 and E >= 1")
-        self.E, self.S = E, S
+        if policy not in ("fifo", "lru", "belady"):
+            raise ValueError("unknown policy")
+        self.E, self.S, self.policy = E, S, policy
         self.slot_key = [-1] * S        # layer*E + e held by each slot
-        self.cursor = 0                 # next slot to overwrite == the oldest load
+        self.cursor = 0                 # fifo: next slot to overwrite == the oldest load
         self.last_use = [-1] * S        # global wave that last computed from the slot
         self.g = 0                      # next global wave index
+        self.clock = 0                  # counts loads and hits
+        self.loaded_at = [-1] * S       # clock value of the load that filled the slot
+        self.touched_at = [-1] * S      # clock value of the slot's last load or hit
 
-    def plan_layer(self, layer: int, ids, W: int) -> LayerPlan:
+    def _victim(self, in_wave, next_use):
+        """Slot to overwrite, or -1 when every slot belongs to the wave being assembled."""
+        free = [s for s in range(self.S) if s not in in_wave]
+        if not free:
+            return -1
+        for s in free:
+            if self.slot_key[s] == -1:
+                return s
+        if self.policy == "lru":
+            return min(free, key=lambda s: self.touched_at[s])
+        best = free[0]
+        for s in free[1:]:
+            a, b = next_use(self.slot_key[s]), next_use(self.slot_key[best])
+            if a > b or (a == b and self.loaded_at[s] < self.loaded_at[best]):
+                best = s
+        return best
+
+    def plan_layer(self, layer: int, ids, W: int, future_keys=()) -> LayerPlan:
         E, S = self.E, self.S
         if not 1 <= W <= S:
             raise ValueError("need 1 <= W <= S")
@@ -172,39 +219,61 @@ class PoolState:
         plan.counts, plan.offsets = token_counts(ids, E)      # raises on a bad id before any change
 
         # Algorithm 1: walk the tokens in order and check each token's expert.
-        seen = [False] * E
-        for s in range(T):
-            k = int(ids[s])
-            if not seen[k]:
-                seen[k] = True
-                plan.order.append(k)
+        plan.order = first_appearance(ids, E)
         if not plan.order:
             return plan
+
+        # next use of a resident key, seen from expert number i of this layer: the experts still
+        # to come in this layer are the nearest uses, then the caller's future in its order
+        place = {layer * E + e: j for j, e in enumerate(plan.order)}
+        later = {}
+        for j, k in enumerate(future_keys):
+            later.setdefault(int(k), j)
 
         plan.first_wave = self.g
         deps = {self.g: -1}
         n = 0
         in_wave = set()                 # slots the current wave computes from
-        for e in plan.order:
+
+        def new_wave():
+            nonlocal n, in_wave
+            self.g += 1
+            deps[self.g] = -1
+            n, in_wave = 0, set()
+
+        for i, e in enumerate(plan.order):
             key = layer * E + e
+
+            def next_use(k):
+                if place.get(k, -1) > i:
+                    return place[k] - i
+                return len(plan.order) + later[k] if k in later else NEVER
+
             s = self.slot_key.index(key) if key in self.slot_key else -1
             if s != -1:                                        # on the GPU already
                 if n == W:
-                    self.g += 1
-                    deps[self.g] = -1
-                    n, in_wave = 0, set()
+                    new_wave()
                 plan.hit[e] = 1
             else:                                              # not on the GPU: load it
-                if n == W or self.cursor in in_wave:
-                    self.g += 1
-                    deps[self.g] = -1
-                    n, in_wave = 0, set()
-                s = self.cursor
+                if self.policy == "fifo":
+                    if n == W or self.cursor in in_wave:
+                        new_wave()
+                    s = self.cursor
+                    self.cursor = (self.cursor + 1) % S
+                else:
+                    if n == W:
+                        new_wave()
+                    s = self._victim(in_wave, next_use)
+                    if s == -1:
+                        new_wave()
+                        s = self._victim(in_wave, next_use)
                 plan.evicted_key[e] = self.slot_key[s]
                 self.slot_key[s] = key
-                self.cursor = (self.cursor + 1) % S
+                self.loaded_at[s] = self.clock
                 deps[self.g] = max(deps[self.g], self.last_use[s])
                 plan.hit[e] = 0
+            self.touched_at[s] = self.clock
+            self.clock += 1
             plan.slot[e] = s
             plan.wave[e] = self.g
             in_wave.add(s)
@@ -214,3 +283,29 @@ class PoolState:
         plan.n_waves = self.g - plan.first_wave
         plan.wave_dep = [deps[plan.first_wave + w] for w in range(plan.n_waves)]
         return plan
+
+
+def serve_plans_step(pool: PoolState, batches, i: int, W: int, lookahead: int):
+    """Plans batch i of the stream: what the inference thread does after popping hash table i
+    while the `lookahead` batches behind it (fewer at the end of the stream) wait in the queue."""
+    E = pool.E
+    table = batches[i]
+    visible = batches[i + 1:i + 1 + lookahead]
+    plans = []
+    for l, ids in enumerate(table):
+        future = []
+        for l2 in range(l + 1, len(table)):
+            future += [l2 * E + e for e in first_appearance(table[l2], E)]
+        for other in visible:
+            for l2, ids2 in enumerate(other):
+                future += [l2 * E + e for e in first_appearance(ids2, E)]
+        plans.append(pool.plan_layer(l, ids, W, future))
+    return plans
+
+
+def serve_plans(pool: PoolState, batches, W: int, lookahead: int):
+    """Plans a stream of batches the way the inference thread consumes the hash-table queue.
+
+    batches: list of hash tables, each a list of L id arrays (one per MoE layer), in arrival order.
+    Returns one list of LayerPlan per batch."""
+    return [serve_plans_step(pool, batches, i, W, lookahead) for i in range(len(batches))]

@@ -32,6 +32,35 @@ def read_plan_trace(name="plan_trace.txt"):
     return head["E"], head["S"], head["W"], calls
 
 
+def read_serve_trace(name="serve_trace.txt"):
+    """Returns (head, batches): head has E, S, W, lookahead, policy, fifo_misses; each batch is a
+    list of calls as in read_plan_trace."""
+    head, batches, cur = {}, [], None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, _, v = line.partition(" ")
+            if k in ("E", "S", "W", "lookahead", "fifo_misses"):
+                head[k] = int(v)
+            elif k == "policy":
+                head[k] = v
+            elif k == "batch":
+                batches.append([])
+            elif k == "call":
+                parts = dict(p.split("=") for p in v.split())
+                cur = {"layer": int(parts["layer"]), "ids": _ints(parts["ids"]), "entries": []}
+                batches[-1].append(cur)
+            elif k == "entry":
+                cur["entries"].append(tuple(int(t) for t in v.split()))
+            elif k == "g":
+                cur[k] = int(v)
+            else:
+                cur[k] = _ints(v)
+    return head, batches
+
+
 def read_table2():
     rows = {}
     with open(os.path.join(GOLDEN, "table2_moe_size.txt")) as f:
