@@ -23,7 +23,7 @@
  *  - Every function returns SIDA_OK (0) or a negative sida_status.  On an error nothing has been
  *    enqueued and no bookkeeping has changed.  Faults of work that was already enqueued show up
  *    at the caller's next stream synchronisation, as with any HIP work.
- *  - A context is not thread-safe; use one per serving thread.  All compute of one context must
+ *  - A context is not thread-safe (the hash-table queue calls excepted); use one per serving thread.  All compute of one context must
  *    be enqueued on one stream, all copies on one (other) stream.
  *  - Limits: 1 <= E <= SIDA_MAX_E; d_model and d_ff multiples of 128; 1 <= W <= S.
  */
@@ -45,8 +45,19 @@ typedef enum sida_status {
     SIDA_ENOSPC = -2,   /* workspace or pool smaller than required                            */
     SIDA_ESTATE = -3,   /* pool / host weights not bound, stale plan, calls out of wave order  */
     SIDA_EHIP = -4,     /* a HIP call failed; see sida_last_hip_error()                        */
-    SIDA_ENOMEM = -5    /* host allocation failed                                              */
+    SIDA_ENOMEM = -5,   /* host allocation failed                                              */
+    SIDA_EAGAIN = -6,   /* sida_queue_pop_plan: no hash table arrived within the timeout       */
+    SIDA_ECLOSED = -7   /* hash-table queue closed (and, for a pop, drained)                   */
 } sida_status;
+
+/* Replacement policy of the slot pool.  The paper uses first-in-first-out and notes that other
+ * strategies could be effective too (footnote of Section 4.3). */
+enum { SIDA_POLICY_FIFO = 0,    /* overwrite the oldest load; a hit does not renew an age (default) */
+       SIDA_POLICY_LRU = 1,     /* overwrite the expert loaded or hit longest ago                   */
+       SIDA_POLICY_BELADY = 2   /* overwrite the expert whose next use is farthest in the known
+                                   future (rest of the layer, then the caller's look-ahead);
+                                   ties go to the oldest load                                       */ };
+#define SIDA_QUEUE_CAPACITY 256 /* hash tables the queue holds at most */
 
 typedef struct sida_ctx sida_ctx; /* opaque: host bookkeeping and HIP events only */
 
@@ -142,6 +153,40 @@ int sida_pool_state(const sida_ctx *ctx, int32_t *slot_key, int32_t *cursor, int
  * hold once the plan's copies ran); plans must be made in the order their layers will run.
  * ids_host: host int32 [T], 0 <= T <= max_T.  An id outside [0,E) -> SIDA_EINVAL, state unchanged. */
 int sida_moe_plan(sida_ctx *ctx, int32_t layer, const int32_t *ids_host, int32_t T, sida_plan *out);
+
+/* As sida_moe_plan, with the future the hash-table queue makes known (Section 3.1: tables are
+ * built ahead of the inference thread).  future_keys: host int32 [n_future], keys layer*E+e in
+ * the order they will be needed after this layer (duplicates allowed, the first occurrence
+ * counts).  Only SIDA_POLICY_BELADY looks at it; with no future it degenerates to "oldest load
+ * among the experts this layer does not need any more".  A key outside [0, L*E) -> SIDA_EINVAL. */
+int sida_moe_plan_lookahead(sida_ctx *ctx, int32_t layer, const int32_t *ids_host, int32_t T,
+                            const int32_t *future_keys, int64_t n_future, sida_plan *out);
+/* Chooses the replacement policy and how many queued batches sida_queue_pop_plan may look ahead
+ * at (0..SIDA_QUEUE_CAPACITY).  Only while the pool is empty (after sida_create or
+ * sida_pool_reset), SIDA_ESTATE otherwise.  All policies fill empty slots first and never
+ * overwrite a slot of the wave being assembled. */
+int sida_set_policy(sida_ctx *ctx, int32_t policy, int32_t lookahead_batches);
+
+/* ---- the hash-table queue between the two threads of Algorithm 1 (Section 3.1) --------------
+ * The hash-building thread pushes one table per batch (the expert ids of every MoE layer); the
+ * inference thread pops them in arrival order and gets the batch's residency plans, each layer
+ * planned with the later layers of the batch and the queued batches behind it as its future.
+ * These four calls are safe to use from two threads (one pushing, one popping); every other
+ * call of a context belongs to the inference thread. */
+/* ids_host: host int32 [L, T] row-major, copied.  tag: returned by the pop, for the caller to
+ * find the batch's device buffers.  SIDA_ENOSPC when SIDA_QUEUE_CAPACITY tables wait already,
+ * SIDA_ECLOSED after sida_queue_close, SIDA_EINVAL for an id outside [0,E) (nothing queued). */
+int sida_queue_push(sida_ctx *ctx, int64_t tag, const int32_t *ids_host, int32_t T);
+/* No more tables will come: pops drain the queue, then return SIDA_ECLOSED. */
+int sida_queue_close(sida_ctx *ctx);
+/* Tables waiting (>= 0), or a negative status. */
+int sida_queue_size(sida_ctx *ctx);
+/* Waits up to timeout_ms for a table ("remains idle if H_i is not found", Section 3.1), removes
+ * the oldest one and plans its L layers in order, exactly as L calls of sida_moe_plan_lookahead
+ * would: plans[L] (caller's array) are then run with sida_run_layers.  tag / T may be NULL.
+ * SIDA_EAGAIN on timeout, SIDA_ECLOSED when closed and empty; the pool bookkeeping is untouched
+ * in both cases. */
+int sida_queue_pop_plan(sida_ctx *ctx, int32_t timeout_ms, int64_t *tag, int32_t *T, sida_plan *plans);
 
 /* expert_prefetch(slot_table, host_weights, stream): enqueues, on copy_stream, the host -> pool
  * copies of the experts that local wave `wave` of `plan` misses (one copy of expert_bytes each),

@@ -5,6 +5,9 @@ import ctypes as C
 import os
 
 SIDA_MAX_E = 256
+POLICY_FIFO, POLICY_LRU, POLICY_BELADY = 0, 1, 2
+POLICIES = {"fifo": POLICY_FIFO, "lru": POLICY_LRU, "belady": POLICY_BELADY}
+EAGAIN, ECLOSED = -6, -7
 K_NAMES = ("sort", "gather", "gemm1", "gemm2", "combine", "copy")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -69,6 +72,12 @@ def lib():
         "sida_pool_reset": (C.c_int, [vp]),
         "sida_pool_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
         "sida_moe_plan": (C.c_int, [vp, i32, vp, i32, C.POINTER(SidaPlan)]),
+        "sida_moe_plan_lookahead": (C.c_int, [vp, i32, vp, i32, vp, C.c_int64, C.POINTER(SidaPlan)]),
+        "sida_set_policy": (C.c_int, [vp, i32, i32]),
+        "sida_queue_push": (C.c_int, [vp, C.c_int64, vp, i32]),
+        "sida_queue_close": (C.c_int, [vp]),
+        "sida_queue_size": (C.c_int, [vp]),
+        "sida_queue_pop_plan": (C.c_int, [vp, i32, C.POINTER(C.c_int64), C.POINTER(i32), C.POINTER(SidaPlan)]),
         "sida_expert_prefetch": (C.c_int, [vp, C.POINTER(SidaPlan), i32, vp]),
         "sida_moe_layer_forward": (C.c_int, [vp, C.POINTER(SidaPlan), vp, vp, vp, vp, vp, sz, vp, vp]),
         "sida_run_layers": (C.c_int, [vp, i32, C.POINTER(C.POINTER(SidaPlan)), C.POINTER(vp), C.POINTER(vp),
@@ -170,6 +179,44 @@ class Context:
         T = int(ids_host.shape[0])
         self._ck(lib().sida_moe_plan(self._h, layer, _ptr(ids_host) if T else 0, T, C.byref(plan)), "sida_moe_plan")
         return plan
+
+    def moe_plan_lookahead(self, layer, ids_host, future_keys) -> SidaPlan:
+        """future_keys: contiguous int32 numpy array of keys layer*E+e in the order of their next use."""
+        plan = SidaPlan()
+        T, n = int(ids_host.shape[0]), int(future_keys.shape[0])
+        self._ck(lib().sida_moe_plan_lookahead(self._h, layer, _ptr(ids_host) if T else 0, T,
+                                               _ptr(future_keys) if n else 0, n, C.byref(plan)),
+                 "sida_moe_plan_lookahead")
+        return plan
+
+    def set_policy(self, policy, lookahead_batches=0):
+        self._ck(lib().sida_set_policy(self._h, POLICIES.get(policy, policy), lookahead_batches), "sida_set_policy")
+
+    # ---- hash-table queue
+    def queue_push(self, tag, ids_host):
+        """ids_host: contiguous int32 numpy array [L, T]."""
+        assert ids_host.ndim == 2 and ids_host.shape[0] == self.cfg.L
+        T = int(ids_host.shape[1])
+        self._ck(lib().sida_queue_push(self._h, tag, _ptr(ids_host) if T else 0, T), "sida_queue_push")
+
+    def queue_close(self):
+        self._ck(lib().sida_queue_close(self._h), "sida_queue_close")
+
+    def queue_size(self) -> int:
+        n = lib().sida_queue_size(self._h)
+        if n < 0:
+            raise SidaError(n, "sida_queue_size")
+        return n
+
+    def queue_pop_plan(self, timeout_ms=0):
+        """Returns (tag, T, [SidaPlan] * L); None on timeout; raises SidaError(ECLOSED) when closed and empty."""
+        plans = (SidaPlan * self.cfg.L)()
+        tag, T = C.c_int64(), C.c_int32()
+        rc = lib().sida_queue_pop_plan(self._h, timeout_ms, C.byref(tag), C.byref(T), plans)
+        if rc == EAGAIN:
+            return None
+        self._ck(rc, "sida_queue_pop_plan")
+        return tag.value, T.value, [plans[l] for l in range(self.cfg.L)]
 
     def expert_prefetch(self, plan, wave, copy_stream):
         self._ck(lib().sida_expert_prefetch(self._h, C.byref(plan), wave, _stream(copy_stream)), "sida_expert_prefetch")

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstring>
 #include <new>
 
@@ -369,7 +370,10 @@ int sida_create(const sida_config *cfg, sida_ctx **out)
         c->expert_bytes = (size_t)4 * cfg->d_model * cfg->d_ff;
         c->slot_key.assign(cfg->S, -1);
         c->last_use.assign(cfg->S, -1);
+        c->loaded_at.assign(cfg->S, -1);
+        c->touched_at.assign(cfg->S, -1);
         c->key_slot.assign((size_t)cfg->L * cfg->E, -1);
+        c->next_use.reserve((size_t)cfg->L * cfg->E);
     } catch (const std::bad_alloc &) {
         delete c;
         return SIDA_ENOMEM;
@@ -398,6 +402,8 @@ const char *sida_strerror(int code)
     switch (code) {
         case SIDA_OK: return "ok";
         case SIDA_EINVAL: return "invalid argument";
+        case SIDA_EAGAIN: return "hash-table queue empty (timed out)";
+        case SIDA_ECLOSED: return "hash-table queue closed";
         case SIDA_ENOSPC: return "workspace or pool too small";
         case SIDA_ESTATE: return "call not valid in this state (unbound pool/weights, stale plan or wrong order)";
         case SIDA_EHIP: return "HIP call failed";
@@ -455,6 +461,9 @@ int sida_pool_reset(sida_ctx *c)
     std::fill(c->last_use.begin(), c->last_use.end(), -1);
     std::fill(c->key_slot.begin(), c->key_slot.end(), -1);
     std::fill(c->ready_recorded.begin(), c->ready_recorded.end(), 0);
+    std::fill(c->loaded_at.begin(), c->loaded_at.end(), -1);
+    std::fill(c->touched_at.begin(), c->touched_at.end(), -1);
+    c->clock = 0;
     c->cursor = 0;
     c->next_wave = 0;
     c->prefetched_upto = 0;
@@ -477,7 +486,125 @@ int sida_moe_plan(sida_ctx *c, int32_t layer, const int32_t *ids_host, int32_t T
     if (!c || !out || layer < 0 || layer >= c->cfg.L || T < 0 || T > c->cfg.max_T || (T > 0 && !ids_host))
         return SIDA_EINVAL;
     if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E) return SIDA_ESTATE;   // wave counter exhausted: reset the pool
-    return plan_layer(c, layer, ids_host, T, out);
+    return plan_layer(c, layer, ids_host, T, nullptr, 0, out);
+}
+
+int sida_moe_plan_lookahead(sida_ctx *c, int32_t layer, const int32_t *ids_host, int32_t T,
+                            const int32_t *future_keys, int64_t n_future, sida_plan *out)
+{
+    if (!c || !out || layer < 0 || layer >= c->cfg.L || T < 0 || T > c->cfg.max_T || (T > 0 && !ids_host) ||
+        n_future < 0 || (n_future > 0 && !future_keys))
+        return SIDA_EINVAL;
+    if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E) return SIDA_ESTATE;
+    try {
+        return plan_layer(c, layer, ids_host, T, future_keys, n_future, out);
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
+}
+
+int sida_set_policy(sida_ctx *c, int32_t policy, int32_t lookahead_batches)
+{
+    if (!c || policy < SIDA_POLICY_FIFO || policy > SIDA_POLICY_BELADY || lookahead_batches < 0 ||
+        lookahead_batches > SIDA_QUEUE_CAPACITY)
+        return SIDA_EINVAL;
+    for (int32_t k : c->slot_key)
+        if (k >= 0) return SIDA_ESTATE;              // ages of resident experts would be meaningless
+    c->policy = policy;
+    c->lookahead = lookahead_batches;
+    return SIDA_OK;
+}
+
+// ---- hash-table queue ------------------------------------------------------------------------
+int sida_queue_push(sida_ctx *c, int64_t tag, const int32_t *ids_host, int32_t T)
+{
+    if (!c || T < 0 || T > c->cfg.max_T || (T > 0 && !ids_host)) return SIDA_EINVAL;
+    const int32_t L = c->cfg.L, E = c->cfg.E;
+    QueuedTable q;
+    try {
+        q.tag = tag;
+        q.T = T;
+        q.ids.assign(ids_host, ids_host + (size_t)L * T);
+        q.key_begin.assign(L + 1, 0);
+        std::vector<uint8_t> seen(E);
+        for (int32_t l = 0; l < L; ++l) {
+            std::fill(seen.begin(), seen.end(), 0);
+            for (int32_t t = 0; t < T; ++t) {
+                const int32_t k = q.ids[(size_t)l * T + t];
+                if (k < 0 || k >= E) return SIDA_EINVAL;
+                if (!seen[k]) {
+                    seen[k] = 1;
+                    q.keys.push_back(l * E + k);
+                }
+            }
+            q.key_begin[l + 1] = (int32_t)q.keys.size();
+        }
+        std::lock_guard<std::mutex> lk(c->q_mu);
+        if (c->q_closed) return SIDA_ECLOSED;
+        if (c->queue.size() >= (size_t)SIDA_QUEUE_CAPACITY) return SIDA_ENOSPC;
+        c->queue.push_back(std::move(q));
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
+    c->q_cv.notify_one();
+    return SIDA_OK;
+}
+
+int sida_queue_close(sida_ctx *c)
+{
+    if (!c) return SIDA_EINVAL;
+    {
+        std::lock_guard<std::mutex> lk(c->q_mu);
+        c->q_closed = true;
+    }
+    c->q_cv.notify_all();
+    return SIDA_OK;
+}
+
+int sida_queue_size(sida_ctx *c)
+{
+    if (!c) return SIDA_EINVAL;
+    std::lock_guard<std::mutex> lk(c->q_mu);
+    return (int)c->queue.size();
+}
+
+int sida_queue_pop_plan(sida_ctx *c, int32_t timeout_ms, int64_t *tag, int32_t *T, sida_plan *plans)
+{
+    if (!c || !plans || timeout_ms < 0) return SIDA_EINVAL;
+    const int32_t L = c->cfg.L;
+    if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E * L) return SIDA_ESTATE;
+    QueuedTable q;
+    std::vector<int32_t> behind;                      // activated keys of the batches still queued
+    try {
+        std::unique_lock<std::mutex> lk(c->q_mu);
+        if (!c->q_cv.wait_for(lk, std::chrono::milliseconds(timeout_ms),
+                              [&] { return !c->queue.empty() || c->q_closed; }))
+            return SIDA_EAGAIN;                       // the inference thread stays idle (Section 3.1)
+        if (c->queue.empty()) return SIDA_ECLOSED;
+        q = std::move(c->queue.front());
+        c->queue.pop_front();
+        if (c->policy == SIDA_POLICY_BELADY) {
+            int32_t n = 0;
+            for (const QueuedTable &o : c->queue) {
+                if (n++ == c->lookahead) break;
+                behind.insert(behind.end(), o.keys.begin(), o.keys.end());
+            }
+        }
+        lk.unlock();
+        std::vector<int32_t> future;
+        for (int32_t l = 0; l < L; ++l) {
+            future.assign(q.keys.begin() + q.key_begin[l + 1], q.keys.end());   // later layers of this batch
+            future.insert(future.end(), behind.begin(), behind.end());
+            const int rc = plan_layer(c, l, q.ids.data() + (size_t)l * q.T, q.T, future.data(), (int64_t)future.size(),
+                                      &plans[l]);
+            if (rc != SIDA_OK) return rc;             // cannot happen: ids were checked when pushed
+        }
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
+    if (tag) *tag = q.tag;
+    if (T) *T = q.T;
+    return SIDA_OK;
 }
 
 int sida_expert_prefetch(sida_ctx *c, const sida_plan *plan, int32_t wave, void *copy_stream)

@@ -2,7 +2,10 @@
 #pragma once
 #include <hip/hip_runtime_api.h>
 
+#include <condition_variable>
 #include <cstdint>
+#include <deque>
+#include <mutex>
 #include <vector>
 
 #include "sida_moe.h"
@@ -16,6 +19,15 @@ constexpr int kProfRing = 8192;        // profiled launches between two sida_pro
 struct ProfRec {
     hipEvent_t start, stop;
     int klass;
+};
+
+// One queued hash table (Section 3.1): the expert ids of every MoE layer for one batch.
+struct QueuedTable {
+    int64_t tag = 0;
+    int32_t T = 0;
+    std::vector<int32_t> ids;          // [L][T]
+    std::vector<int32_t> keys;         // activated keys layer*E+e, layer by layer, first-appearance order
+    std::vector<int32_t> key_begin;    // [L+1] range of layer l inside keys
 };
 
 }  // namespace sida
@@ -33,7 +45,13 @@ struct sida_ctx {
     std::vector<int32_t> slot_key;     // [S] key held by each slot, -1 empty
     std::vector<int32_t> key_slot;     // [L*E] slot holding the key, -1 absent
     std::vector<int32_t> last_use;     // [S] global wave that last computes from the slot
-    int32_t cursor = 0;
+    int32_t cursor = 0;                // first-in-first-out: the slot overwritten next
+    int32_t policy = SIDA_POLICY_FIFO;
+    int32_t lookahead = 0;             // queued batches a popped batch may look ahead at
+    int64_t clock = 0;                 // counts loads and hits
+    std::vector<int64_t> loaded_at;    // [S] clock of the load that filled the slot
+    std::vector<int64_t> touched_at;   // [S] clock of the slot's last load or hit
+    std::vector<int64_t> next_use;     // [L*E] scratch of the planner
     int32_t next_wave = 0;             // next global wave index to hand out
     uint32_t epoch = 1;
 
@@ -52,12 +70,19 @@ struct sida_ctx {
     double prof_ms[SIDA_K_COUNT] = {};
     int64_t prof_n[SIDA_K_COUNT] = {};
 
+    // hash-table queue between the hash-building thread (push) and the inference thread (pop)
+    std::mutex q_mu;
+    std::condition_variable q_cv;
+    std::deque<sida::QueuedTable> queue;
+    bool q_closed = false;
+
     int last_hip = 0;
 };
 
 namespace sida {
 
 // Host planner (plan.cpp).
-int plan_layer(sida_ctx *c, int32_t layer, const int32_t *ids, int32_t T, sida_plan *out);
+int plan_layer(sida_ctx *c, int32_t layer, const int32_t *ids, int32_t T, const int32_t *future,
+               int64_t n_future, sida_plan *out);
 
 }  // namespace sida
