@@ -59,6 +59,23 @@ class MoERunner:
     def run(self, plans, xs, idss, alphas, ys):
         self.ctx.run_layers(plans, xs, idss, alphas, ys, self.workspace, self.compute, self.copy)
 
+    # ---- serving loop (Algorithm 1): the hash-building side pushes, the inference side pops and runs
+    def push_table(self, tag: int, ids_host: np.ndarray):
+        """ids_host: int32 [L, T], the batch's hash table.  Safe to call from another thread."""
+        self.ctx.queue_push(tag, np.ascontiguousarray(ids_host, dtype=np.int32))
+
+    def serve_next(self, lookup, timeout_ms=1000):
+        """Pops the oldest hash table, plans it and enqueues its L layers.  lookup(tag) returns the
+        batch's device tensors (xs, idss, alphas, ys), each a list of L.  Returns (tag, plans), or
+        None when no table arrived within the timeout."""
+        got = self.ctx.queue_pop_plan(timeout_ms)
+        if got is None:
+            return None
+        tag, _, plans = got
+        xs, idss, alphas, ys = lookup(tag)
+        self.ctx.run_layers(plans, xs, idss, alphas, ys, self.workspace, self.compute, self.copy)
+        return tag, plans
+
     def sync(self):
         torch.cuda.synchronize(self.dev)      # every stream of the device
 

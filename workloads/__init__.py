@@ -26,6 +26,7 @@ import numpy as np
 BASE_SEED = 20231018
 
 STREAM_X, STREAM_IDS, STREAM_GATE, STREAM_PERM, STREAM_W0 = 0, 1, 2, 3, 4
+STREAM_BATCH_IDS = 1000   # ids of batch b of a stream: seed sequence [base, cfg, layer, 1000, b]
 
 
 @dataclass(frozen=True)
@@ -129,6 +130,27 @@ def gen_ids(wl: Workload, layer: int, T: int | None = None) -> np.ndarray:
     rank = np.searchsorted(cdf, g.random(T), side="right")
     rank = np.minimum(rank, wl.E - 1)
     return expert_permutation(wl, layer)[rank].astype(np.int32)
+
+
+def gen_batch_ids(wl: Workload, batch: int, T: int) -> np.ndarray:
+    """Hash table of one batch of a stream (Section 3.1): predicted expert ids of T tokens for every
+    MoE layer, int32 [L, T].  Same popularity law and per-layer expert permutation as ``gen_ids`` -
+    so the experts that are popular in one batch are popular in the next, which is what makes a
+    slot pool hit across batches - with an independent draw per (batch, layer).  With T around 100
+    and Zipf(1.0) over 128 experts a batch activates about 35-40 % of a layer's experts, the
+    sentence-level sparsity Section 2.3 reports for Switch-base-128."""
+    out = np.empty((wl.L, T), dtype=np.int32)
+    for layer in range(wl.L):
+        g = np.random.Generator(np.random.PCG64(np.random.SeedSequence(
+            [BASE_SEED, wl.index, layer, STREAM_BATCH_IDS, batch])))
+        if wl.zipf_s is None:
+            out[layer] = g.integers(0, wl.E, T)
+            continue
+        p = np.arange(1, wl.E + 1, dtype=np.float64) ** (-float(wl.zipf_s))
+        cdf = np.cumsum(p / p.sum())
+        rank = np.minimum(np.searchsorted(cdf, g.random(T), side="right"), wl.E - 1)
+        out[layer] = expert_permutation(wl, layer)[rank]
+    return out
 
 
 def gen_expert_block(wl: Workload, layer: int, e: int, out: np.ndarray | None = None) -> np.ndarray:
