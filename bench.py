@@ -126,6 +126,56 @@ def cpu_baseline(wl, r, ins, budget_tokens):
             "sample": f"{done} tokens = the first {layers} layer(s) of {wl.name} (grouping + Eq. 1 per token), {dt:.1f} s"}
 
 
+def serve_leg(wl, hw, S, W, policy, look, n_batches, warm, T_b):
+    """Algorithm 1 in full on a stream of small batches: a producer thread pushes hash tables, the
+    main thread pops, plans and runs them; the slot pool persists across batches.  Steady state:
+    the first `warm` batches fill the pool and are not timed."""
+    import threading
+
+    import numpy as np
+    import torch
+    from paper_2310_18859_amd.runner import MoERunner
+    from workloads import gen_batch_ids, gen_gate, gen_x
+
+    r = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, S, W, T_b)
+    r.host_weights = hw
+    base = hw.data_ptr()
+    r.ctx.bind_host_weights([base + i * r.expert_bytes for i in range(wl.L * wl.E)], keep=hw)
+    r.ctx.set_policy(policy, look)
+    tables = [gen_batch_ids(wl, b, T_b) for b in range(n_batches)]
+    shared = [r.to_device(gen_x(wl, l, T_b), tables[0][l], gen_gate(wl, l, T_b)) for l in range(wl.L)]
+    xs, alphas, ys = [t[0] for t in shared], [t[2] for t in shared], [t[3] for t in shared]
+    ids_dev = [[torch.from_numpy(t[l]).to(r.dev) for l in range(wl.L)] for t in tables]
+    r.sync()
+
+    def producer():                                   # the hash-building thread: always ahead
+        for b, t in enumerate(tables):
+            r.push_table(b, t)
+        r.ctx.queue_close()
+
+    th = threading.Thread(target=producer)
+    th.start()
+    th.join()                                         # n_batches <= queue capacity: the look-ahead is always full
+    misses = active = 0
+    t0 = None
+    for b in range(n_batches):
+        if b == warm:
+            r.sync()
+            t0 = time.perf_counter()
+        tag, plans = r.serve_next(lambda t: (xs, ids_dev[t], alphas, ys), 1000)
+        if b >= warm:
+            misses += sum(p.n_miss for p in plans)
+            active += sum(p.n_active for p in plans)
+    r.sync()
+    dt = time.perf_counter() - t0
+    timed = n_batches - warm
+    r.close()
+    return {"policy": policy, "lookahead_batches": look, "pool_slots": S, "wave_experts": W,
+            "tokens_per_s": timed * wl.L * T_b / dt, "ms_per_batch": 1e3 * dt / timed,
+            "hit_rate": 1.0 - misses / max(active, 1), "expert_loads_per_batch": misses / timed,
+            "activated_per_batch": active / timed, "h2d_GBps": misses * wl.expert_bytes / dt / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +191,10 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; 0 = as defined)")
     ap.add_argument("--zipf", type=float, default=None, help="override the Zipf exponent (0 = uniform ids)")
+    ap.add_argument("--serve", choices=["off", "short", "sweep"], default="short",
+                    help="stream-of-batches leg: a few pool sizes and policies (short) or the full table (sweep)")
+    ap.add_argument("--serve-tokens", type=int, default=128, help="tokens per batch of the stream")
+    ap.add_argument("--serve-batches", type=int, default=120)
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1")
@@ -221,6 +275,23 @@ def main():
             log(f"[bench] resident, no per-launch timing events: {1e3 * dt2u / a.resident_steps:.3f} ms/step")
         r2.close()
 
+    # ---- the cross-batch serving loop (Algorithm 1 in full) on sentence-sized batches ----------
+    serving = None
+    if a.serve != "off" and a.only == "both" and not a.tokens and wl.L * wl.E > wl.S:
+        LE = wl.L * wl.E
+        sizes = [LE // 8, LE // 4, LE // 2] if a.serve == "short" else [LE // 16, LE // 8, LE // 4, 3 * LE // 8, LE // 2, 3 * LE // 4, LE]
+        rows = []
+        for S in sizes:
+            for policy, look in (("fifo", 0), ("lru", 0), ("belady", 8)):
+                W = max(1, min(wl.E, S // 2))
+                row = serve_leg(wl, hw, S, W, policy, look,
+                                a.serve_batches, a.serve_batches // 3, a.serve_tokens)
+                rows.append(row)
+                log(f"[bench] serve S={S} {policy}: {row['tokens_per_s']:.3e} tok/s, hit rate {row['hit_rate']:.3f}, "
+                    f"{row['expert_loads_per_batch']:.1f} loads/batch")
+        serving = {"workload": f"{wl.name}: stream of {a.serve_batches} batches of {a.serve_tokens} tokens, "
+                               f"first {a.serve_batches // 3} untimed", "rows": rows}
+
     # ---- K-b on many-token experts alone (every expert far above the MFMA/HBM ridge) ---------
     large_m = None
     if a.only == "both" and not a.tokens:
@@ -292,6 +363,8 @@ def main():
             e["h2d"] = {"achieved": h2d, "peak": H2D_PEAK_GBS, "unit": "GB/s", "frac": h2d / H2D_PEAK_GBS,
                         "note": "expert bytes copied per step / wall time per step"}
         line[mode] = e
+    if serving:
+        line["serving"] = serving
     if large_m:
         large_m["roofline"] = roofline_of(large_m["kernels"], "resident", name=large_m["workload"], prefer="mfma")
         line["kb_large_m"] = large_m
