@@ -273,6 +273,18 @@ def main():
             dt2u, _, _ = time_steps(r2, wl, dev2, ids_host, a.resident_steps, 2)
             result["resident"]["dt_unprofiled"] = dt2u
             log(f"[bench] resident, no per-launch timing events: {1e3 * dt2u / a.resident_steps:.3f} ms/step")
+        # the same steps with gather / combine folded into the GEMMs
+        r2.ctx.set_fusion(True)
+        r2.ctx.profile_enable(not a.no_profile)
+        dt3f, prof3f, _ = time_steps(r2, wl, dev2, ids_host, a.resident_steps, 2)
+        result["resident_fused"] = {"dt": dt3f, "kernels": kernel_report(wl, prof3f, a.resident_steps,
+                                                                        {"loads": 0, "active_experts": active})}
+        if not a.no_profile:
+            r2.ctx.profile_enable(False)
+            dt3u, _, _ = time_steps(r2, wl, dev2, ids_host, a.resident_steps, 2)
+            result["resident_fused"]["dt_unprofiled"] = dt3u
+            log(f"[bench] resident, fused dispatch/combine: {1e3 * dt3f / a.resident_steps:.3f} ms/step "
+                f"({1e3 * dt3u / a.resident_steps:.3f} without timing events)")
         r2.close()
 
     # ---- the cross-batch serving loop (Algorithm 1 in full) on sentence-sized batches ----------
@@ -347,7 +359,7 @@ def main():
 
     line["roofline"] = roofline_of(main["kernels"], main_mode)
     line["cpu_baseline"] = cpu
-    for mode in ("streaming", "resident"):
+    for mode in ("streaming", "resident", "resident_fused"):
         if mode not in result:
             continue
         st = a.steps if mode == "streaming" else a.resident_steps

@@ -107,6 +107,7 @@ typedef struct sida_ws_layout {
     size_t y_perm;      /* bf16  [T, d_model]           expert outputs, perm order            */
     size_t tiles;       /* int32 [4 * (T/128 + E + 1)]  token-tile descriptors of the grouped FFN */
     size_t sink;        /* 64 KiB scratch: absorbs the grouped FFN's stores of rows past a tile's end */
+    size_t gate_perm;   /* fp32  [T]   gate_perm[r] = alpha[perm[r]]   (fused path only)      */
     size_t total;       /* bytes needed                                                       */
 } sida_ws_layout;
 
@@ -215,6 +216,15 @@ int sida_moe_layer_forward(sida_ctx *ctx, const sida_plan *plan, const void *x_d
                            const int32_t *ids_dev, const float *alpha_dev, void *y_dev,
                            void *workspace_dev, size_t workspace_bytes, void *compute_stream,
                            void *copy_stream);
+
+/* Folds the permute-gather into the first GEMM's token-row loads (rows are read from x through
+ * the sort's index, x_perm is never written) and the gate-weighted scatter-combine into the second
+ * GEMM's result stores (with top-1 routing every y row is written exactly once, by the tile that
+ * holds its token; y_perm is never written).  Same arithmetic, bit-identical y; two launches and
+ * about two thirds of the dispatch/combine HBM traffic less per layer.  Affects
+ * sida_moe_layer_forward / sida_run_layers only; the single-stage calls keep the separate passes.
+ * Off by default.  May be switched between layer calls. */
+int sida_set_fusion(sida_ctx *ctx, int32_t on);
 
 /* Convenience: forwards n consecutive planned layers, keeping the copy stream one wave ahead of
  * the compute across layer boundaries too (the first wave of layer i+1 is copied while the last

@@ -42,7 +42,7 @@ class SidaPlan(C.Structure):
 
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
-                ("counts", "offsets", "block_hist", "perm", "inv", "x_perm", "h", "y_perm", "tiles", "sink", "total")]
+                ("counts", "offsets", "block_hist", "perm", "inv", "x_perm", "h", "y_perm", "tiles", "sink", "gate_perm", "total")]
 
 
 _LIB = None
@@ -74,6 +74,7 @@ def lib():
         "sida_moe_plan": (C.c_int, [vp, i32, vp, i32, C.POINTER(SidaPlan)]),
         "sida_moe_plan_lookahead": (C.c_int, [vp, i32, vp, i32, vp, C.c_int64, C.POINTER(SidaPlan)]),
         "sida_set_policy": (C.c_int, [vp, i32, i32]),
+        "sida_set_fusion": (C.c_int, [vp, i32]),
         "sida_queue_push": (C.c_int, [vp, C.c_int64, vp, i32]),
         "sida_queue_close": (C.c_int, [vp]),
         "sida_queue_size": (C.c_int, [vp]),
@@ -188,6 +189,9 @@ class Context:
                                                _ptr(future_keys) if n else 0, n, C.byref(plan)),
                  "sida_moe_plan_lookahead")
         return plan
+
+    def set_fusion(self, on: bool):
+        self._ck(lib().sida_set_fusion(self._h, 1 if on else 0), "sida_set_fusion")
 
     def set_policy(self, policy, lookahead_batches=0):
         self._ck(lib().sida_set_policy(self._h, POLICIES.get(policy, policy), lookahead_batches), "sida_set_policy")

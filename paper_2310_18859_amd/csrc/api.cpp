@@ -60,6 +60,7 @@ void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
     o->y_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
     o->tiles = take(sizeof(TileDesc) * max_tiles(cfg, T));
     o->sink = take(kGemmSinkBytes);
+    o->gate_perm = take(sizeof(float) * (size_t)T);
     o->total = off;
 }
 
@@ -69,6 +70,7 @@ struct Ws {
     TileDesc *tiles;
     int32_t max_tiles;
     void *sink;
+    float *gate_perm;
 };
 
 Ws carve(const sida_config &cfg, int32_t T, void *base)
@@ -79,7 +81,7 @@ Ws carve(const sida_config &cfg, int32_t T, void *base)
     return Ws{(int32_t *)(b + l.counts), (int32_t *)(b + l.offsets), (int32_t *)(b + l.block_hist),
               (int32_t *)(b + l.perm),   (int32_t *)(b + l.inv),     b + l.x_perm,
               b + l.h,                   b + l.y_perm,               (TileDesc *)(b + l.tiles),
-              (int32_t)max_tiles(cfg, T), b + l.sink};
+              (int32_t)max_tiles(cfg, T), b + l.sink, (float *)(b + l.gate_perm)};
 }
 
 int check_plan(const sida_ctx *c, const sida_plan *p)
@@ -222,15 +224,17 @@ int prefetch_allowed(const sida_ctx *c, const sida_plan *p, int32_t w)
     return SIDA_OK;
 }
 
+// alpha != NULL: the fused path - the gate values are moved along with the sort and the gather
+// pass is left to GEMM 1.
 int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, const Ws &ws, const LayerTable *tbl,
-                    hipStream_t st)
+                    hipStream_t st, const float *alpha = nullptr)
 {
     {
         Timed tm(c, SIDA_K_SORT, st);
         HIP_TRY(c, (hipError_t)launch_sort(ids, T, c->cfg.E, ws.counts, ws.offsets, ws.block_hist, ws.perm, ws.inv, tbl,
-                                           ws.tiles, ws.max_tiles, st));
+                                           ws.tiles, ws.max_tiles, st, alpha, ws.gate_perm));
     }
-    {
+    if (!alpha) {
         TimedKernel tk(c, SIDA_K_GATHER);
         HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st, tk.get()));
     }
@@ -244,18 +248,22 @@ int launch_tiles(sida_ctx *c, const LayerSchedule &s, const Ws &ws, hipStream_t 
     return SIDA_OK;
 }
 
-int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws, hipStream_t st)
+// x, y != NULL: the fused path - GEMM 1 reads x through perm, GEMM 2 scales by the gate and writes y.
+int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws, hipStream_t st,
+                    const void *x = nullptr, void *y = nullptr)
 {
     const TileDesc *tiles = ws.tiles + s.tile_begin[w];
     {
         TimedKernel tk(c, SIDA_K_GEMM1);
-        HIP_TRY(c, (hipError_t)launch_ffn_gemm1(ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get()));
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm1(x ? x : ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
+                                                x ? ws.perm : nullptr));
     }
     {
         TimedKernel tk(c, SIDA_K_GEMM2);
-        HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get()));
+        HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, y ? y : ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
+                                                y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr));
     }
     return SIDA_OK;
 }
@@ -322,7 +330,9 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
         const Ws ws = carve(c->cfg, p->T, ws_dev);
         LayerSchedule sched;
         build_schedule(p, &sched);
-        rc = launch_dispatch(c, a.x, a.ids, p->T, ws, &sched.tbl, compute);     // also expands sched.tbl into tiles
+        const bool fused = c->fused;
+        rc = launch_dispatch(c, a.x, a.ids, p->T, ws, &sched.tbl, compute,      // also expands sched.tbl into tiles
+                             fused ? a.alpha : nullptr);
         if (rc) return rc;
         for (int32_t w = 0; w < p->n_waves; ++w) {
             const int32_t g = p->first_wave + w;
@@ -336,13 +346,13 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
             }
             const int ring = g % kEventRing;
             if (c->ready_recorded[ring]) HIP_TRY(c, hipStreamWaitEvent(compute, c->ev_ready[ring], 0));
-            rc = launch_wave_ffn(c, sched, w, ws, compute);
+            rc = launch_wave_ffn(c, sched, w, ws, compute, fused ? a.x : nullptr, fused ? a.y : nullptr);
             if (rc) return rc;
             if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_done[ring]));
             HIP_TRY(c, hipEventRecord(c->ev_done[ring], compute));
             c->forwarded_upto = g + 1;
         }
-        {
+        if (!fused) {
             TimedKernel tk(c, SIDA_K_COMBINE);
             HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute, tk.get()));
         }
@@ -501,6 +511,13 @@ int sida_moe_plan_lookahead(sida_ctx *c, int32_t layer, const int32_t *ids_host,
     } catch (const std::bad_alloc &) {
         return SIDA_ENOMEM;
     }
+}
+
+int sida_set_fusion(sida_ctx *c, int32_t on)
+{
+    if (!c) return SIDA_EINVAL;
+    c->fused = on != 0;
+    return SIDA_OK;
 }
 
 int sida_set_policy(sida_ctx *c, int32_t policy, int32_t lookahead_batches)

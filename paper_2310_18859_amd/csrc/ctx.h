@@ -63,6 +63,8 @@ struct sida_ctx {
     std::vector<uint8_t> ready_recorded;  // ring: wave g recorded a ready event (it had misses)
     bool events_made = false;
 
+    bool fused = false;                // gather / combine folded into the grouped GEMMs
+
     // kernel timing
     bool profiling = false;
     std::vector<sida::ProfRec> prof_pool;

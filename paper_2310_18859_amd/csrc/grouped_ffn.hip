@@ -53,6 +53,13 @@ __device__ __forceinline__ void load_to_lds(const void *gsrc, void *lds_dst)
                                      (__attribute__((address_space(3))) void *)lds_dst, 16, 0, 0);
 }
 
+// One dword per lane: lane i's word lands at offset 4*i of the 256-byte window at lds_dst.
+__device__ __forceinline__ void load_word_to_lds(const void *gsrc, void *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_dst, 4, 0, 0);
+}
+
 // Output tile t of a launch -> (token tile, weight-row tile).
 //
 // What decides the speed is the number of bytes that miss the L2: every XCD has its own 4 MiB L2,
@@ -103,12 +110,28 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_t
 // loads with running pointers, the LDS fragment reads and the MFMAs - no tile bookkeeping.
 //
 // BM x BN is the output tile (tokens x weight rows), WM x WN the wavefront grid (8 wavefronts).
-template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
+//
+// FUSE selects what the token rows are addressed through:
+//   kPlain    A rows and C rows are the tile's rows row0 .. row0+rows-1 (x_perm -> h -> y_perm);
+//   kGather   A is x in token order: row r of the tile is read from x[perm[row0 + r]] (GEMM 1
+//             without a separate gather pass);
+//   kScatter  C is y in token order: row r of the tile is scaled by gate_perm[row0 + r] (fp32
+//             product of the bf16-rounded result, one more rounding to bf16 - the arithmetic of
+//             the separate combine pass) and written to y[perm[row0 + r]] (GEMM 2 without a
+//             separate combine pass; top-1 routing writes every y row exactly once).
+// The row maps are fetched into a small private LDS buffer per wavefront with the same direct
+// loads as the tiles (no register-returning vector loads, which would make every use wait for
+// all older tile loads): kExtra more operations per tile in the wait counts.
+enum { kPlain = 0, kGather = 1, kScatter = 2 };
+
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU, int FUSE>
 __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__restrict__ A, __bf16 *__restrict__ C,
                                                                const char *__restrict__ pool, size_t expert_bytes,
                                                                size_t w_off, const TileDesc *__restrict__ tiles,
                                                                int m_tiles, int m_tall, int nw, int N, int K,
-                                                               char *__restrict__ sink)
+                                                               char *__restrict__ sink,
+                                                               const int32_t *__restrict__ perm,
+                                                               const float *__restrict__ gate_perm)
 {
     constexpr int NW = WM * WN;
     constexpr int kRowBytes = BK * 2;                         // a tile row in LDS: BK bf16 (128 or 64 bytes)
@@ -117,13 +140,16 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     constexpr int kRingBytes = STAGES * kStageBytes;
     constexpr int LOADS = (BM + BN) / (RPL * NW);             // direct loads per thread per K-step
+    constexpr int kSideBytes = FUSE == kPlain ? 0 : 512;      // per wavefront: row maps of a tile
+    constexpr int kExtra = FUSE == kPlain ? 0 : 2;            // direct loads per thread per tile for them
+    static_assert(FUSE == kPlain || (BM == 128 && WM == 2), "row maps are laid out for 128-row tiles, two wavefront rows");
     static_assert(BK == 64 || BK == 32, "K step");
     constexpr int MI = BM / (32 * WM);                        // 32-row MFMA blocks per wavefront along tokens
     constexpr int NI = BN / (32 * WN);                        //   ... along weight rows
     constexpr int KS = BK / 16;                               // MFMA K sub-steps per stage
     constexpr int STORES = MI * NI * 2;                       // result stores per thread per tile (16 bytes each)
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && (BM + BN) % (RPL * NW) == 0 && BM % RPL == 0, "tile");
-    static_assert(STAGES >= 2 && (STAGES - 2) * LOADS + STORES <= 63, "vmcnt range");
+    static_assert(STAGES >= 2 && (STAGES - 2) * LOADS + STORES + kExtra <= 63, "vmcnt range");
     static_assert(NW * 64 * 16 <= kGemmSinkBytes, "sink size");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -153,14 +179,22 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         *c = Coord{td.row0, td.rows, nt};
         return td.slot;
     };
+    char *side = lds + kRingBytes + wv * kSideBytes;          // this wavefront's row maps (FUSE != kPlain)
+    // kGather: perm[row0 .. row0+127] of a tile (rows past its end repeat the last one) -> side[0..127]
+    auto fetch_rows_in = [&](const Coord &c) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            load_word_to_lds(perm + c.row0 + min(i * 64 + lane, c.rows - 1), side + i * 256);
+    };
     auto point = [&](const Coord &c, int slot, const char *(&p)[LOADS]) {
         const char *Wt = pool + (size_t)slot * expert_bytes + w_off + (size_t)c.nt * BN * K * 2;
-        const char *At = reinterpret_cast<const char *>(A) + (size_t)c.row0 * K * 2;
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const int r = (wv * LOADS + j) * RPL + sub_row;   // row in the stage
-            p[j] = r < BM ? At + (size_t)min(r, c.rows - 1) * K * 2 + piece * 16    // rows past the end re-read
-                          : Wt + (size_t)(r - BM) * K * 2 + piece * 16;              // the last one
+            const int ra = min(r, c.rows - 1);                // rows past the end re-read the last one
+            const int src = FUSE == kGather ? reinterpret_cast<const int *>(side)[ra] : c.row0 + ra;
+            p[j] = r < BM ? reinterpret_cast<const char *>(A) + (size_t)src * K * 2 + piece * 16
+                          : Wt + (size_t)(r - BM) * K * 2 + piece * 16;
         }
     };
     int wr_off = 0;                                           // ring offset of the stage filled next
@@ -226,12 +260,20 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     constexpr int RPI = 64 / LPR;                             // rows per store instruction
     static_assert(STORES == MI * (32 / RPI), "store count");
     static_assert(NW * 32 * kOutPitch <= kStageBytes, "staging fits in a stage");
+    // kScatter: this wavefront's 64 rows of the tile: perm -> side[0..63], gate_perm -> side[64..127]
+    auto fetch_rows_out = [&](const Coord &c) {
+        const int r = c.row0 + min(wm * 64 + lane, c.rows - 1);
+        load_word_to_lds(perm + r, side);
+        load_word_to_lds(gate_perm + r, side + 256);
+    };
     auto store_tile = [&](const Coord &c) {
         __builtin_amdgcn_s_barrier();                         // everyone is done reading the last stage
         char *stg = lds + (rd_off == 0 ? kRingBytes - kStageBytes : rd_off - kStageBytes) + wv * (32 * kOutPitch);
         const int seg = lane % LPR, srow = lane / LPR;
 #pragma unroll
         for (int im = 0; im < MI; ++im) {
+            float gate = 1.f;
+            if (FUSE == kScatter) gate = reinterpret_cast<const float *>(side + 256)[im * 32 + frag_row];
 #pragma unroll
             for (int in = 0; in < NI; ++in)
 #pragma unroll
@@ -242,6 +284,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                         float v = acc[in][im][q * 4 + j];
                         if (RELU) v = v > 0.f ? v : 0.f;
                         o[j] = (__bf16)v;
+                        if (FUSE == kScatter) o[j] = (__bf16)(gate * (float)o[j]);
                     }
                     *reinterpret_cast<bf16x4 *>(stg + frag_row * kOutPitch + (in * 32 + q * 8 + half * 4) * 2) = o;
                 }
@@ -251,7 +294,8 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                 const int r = i * RPI + srow;
                 const int m = wm * (BM / WM) + im * 32 + r;
                 const bf16x8 v = *reinterpret_cast<const bf16x8 *>(stg + r * kOutPitch + seg * 16);
-                __bf16 *dst = m < c.rows ? C + (size_t)(c.row0 + m) * N + (size_t)c.nt * BN + wn * (BN / WN) + seg * 8
+                const int out_row = FUSE == kScatter ? reinterpret_cast<const int *>(side)[im * 32 + r] : c.row0 + m;
+                __bf16 *dst = m < c.rows ? C + (size_t)out_row * N + (size_t)c.nt * BN + wn * (BN / WN) + seg * 8
                                          : reinterpret_cast<__bf16 *>(sink) + (size_t)tid * 8;
                 *reinterpret_cast<bf16x8 *>(dst) = v;
             }
@@ -262,6 +306,10 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     Coord cc, nc;
     int slot = locate(0, &cc);
     nc = cc;
+    if (FUSE == kGather) {                                    // the first tile's row map is needed at once
+        fetch_rows_in(cc);
+        wait_loads<0>();
+    }
     point(cc, slot, cur);
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue(cur);          // K-steps 0 .. STAGES-2 of the first tile
@@ -271,11 +319,16 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         const bool has_next = t + 1 < n;
         int next_slot = 0;
         if (has_next) next_slot = locate(t + 1, &nc);         // used only after the first part of the K loop
+        // row maps: of the next tile's token rows (read by point() below), or of this tile's result
+        // rows (read by store_tile()); issued by every thread on every tile so that the waits can
+        // count them.  The previous reads of the buffer are behind this wavefront.
+        if (FUSE == kGather) fetch_rows_in(nc);
+        if (FUSE == kScatter) fetch_rows_out(cc);
         // ---- K-steps whose loads still belong to this tile.  For the first STAGES-1 steps after a
         // tile's result stores those may be outstanding too (vector memory operations of a
         // wavefront complete in issue order, stores included).
         for (int k = 0; k <= nk - STAGES; ++k) {
-            if (t > 0 && k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES>();
+            if (t > 0 && k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES + kExtra>();
             else wait_loads<(STAGES - 2) * LOADS>();
             __builtin_amdgcn_s_barrier();                     // everyone's pieces of this stage are in LDS, and
                                                               // everyone is done reading the stage refilled next
@@ -284,10 +337,12 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         }
         // ---- last STAGES-1 K-steps: the loads already fetch the next tile
         if (has_next) {
+            // the row map of the next tile is in LDS once a wait of step STAGES-1 or later has passed
+            if (FUSE == kGather && nk < 2 * STAGES - 1) wait_loads<0>();
             point(nc, next_slot, cur);                        // all loads of this tile have been issued
 #pragma unroll
             for (int k = 0; k < STAGES - 1; ++k) {
-                if (t > 0 && nk - (STAGES - 1) + k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES>();
+                if (t > 0 && nk - (STAGES - 1) + k < STAGES - 1) wait_loads<(STAGES - 2) * LOADS + STORES + kExtra>();
                 else wait_loads<(STAGES - 2) * LOADS>();
                 __builtin_amdgcn_s_barrier();
                 issue(cur);
@@ -301,6 +356,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                 multiply_stage();
             }
         }
+        if (FUSE == kScatter && has_next && nk < STAGES) wait_loads<0>();   // as above, for this tile's row maps
         store_tile(cc);
         clear();
         cc = nc;
@@ -330,15 +386,16 @@ int persistent_grid()
 #define KB2 64
 #define ST2 4
 #endif
-template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
-int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
-           int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, hipStream_t st, const LaunchEvents *ev)
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU, int FUSE>
+int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
+              int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
+              hipStream_t st, const LaunchEvents *ev)
 {
-    constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2;
+    constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2 + (FUSE == kPlain ? 0 : WM * WN * 512);
     static_assert(kLdsBytes <= 160 * 1024, "LDS");
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU, FUSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
@@ -355,38 +412,53 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
     while (n_tiles_n % nw) --nw;
     const int total = m_tiles * n_tiles_n;
     const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
-    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU>), dim3(grid), dim3(WM * WN * 64), kLdsBytes,
+    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU, FUSE>), dim3(grid), dim3(WM * WN * 64), kLdsBytes,
                           st, ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, (const __bf16 *)A, (__bf16 *)C, pool,
-                          expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink);
+                          expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink, perm, gate_perm);
     return (int)hipGetLastError();
+}
+
+// GEMM 1 gathers when a row map is given, GEMM 2 scatters.
+template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
+int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
+           int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
+           hipStream_t st, const LaunchEvents *ev)
+{
+    if (!perm)
+        return launch_as<BM, BN, BK, WM, WN, STAGES, RELU, kPlain>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N,
+                                                                   K, sink, nullptr, nullptr, st, ev);
+    return launch_as<BM, BN, BK, WM, WN, STAGES, RELU, RELU ? kGather : kScatter>(A, C, pool, expert_bytes, w_off, tiles,
+                                                                                  m_tiles, m_tall, N, K, sink, perm,
+                                                                                  gate_perm, st, ev);
 }
 
 }  // namespace
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev)
+                     const LaunchEvents *ev, const int32_t *perm)
 {
+    const float *gate_perm = nullptr;
     // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
     // Switch shape, other widths fall back to 128
     if (F % 256 == 0 && d >= KB1 * (ST1 - 1))
-        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
+        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
     if (F % 256 == 0 && d >= 128)
-        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
+        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
     if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
-        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
-    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, st, ev);
+        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
+    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev)
+                     const LaunchEvents *ev, const int32_t *perm, const float *gate_perm)
 {
     if (F < KB2 * (ST2 - 1))
         return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                                m_tall, d, F, sink, st, ev);
+                                                m_tall, d, F, sink, perm, gate_perm, st, ev);
     return launch<128, 128, KB2, 2, 4, ST2, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                            m_tall, d, F, sink, st, ev);
+                                            m_tall, d, F, sink, perm, gate_perm, st, ev);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------

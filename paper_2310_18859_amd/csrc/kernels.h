@@ -33,9 +33,10 @@ struct LaunchEvents {
 // K-a: stable counting sort of T tokens by expert id.
 //   ids int32[T] -> counts[E], offsets[E+1], perm[T], inv[T];  block_hist is scratch [n_chunks*E].
 // When tbl is given (may be NULL) it is also expanded into token tiles, see launch_build_tiles.
+// With alpha (may be NULL) the gate values are moved along: gate_perm[r] = alpha[perm[r]].
 int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32_t *offsets,
                 int32_t *block_hist, int32_t *perm, int32_t *inv, const LayerTable *tbl, TileDesc *tiles,
-                int32_t max_tiles, hipStream_t st);
+                int32_t max_tiles, hipStream_t st, const float *alpha = nullptr, float *gate_perm = nullptr);
 // K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st,
                   const LaunchEvents *ev = nullptr);
@@ -43,12 +44,16 @@ int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void
 // tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles); the
 // first m_tall of them belong to experts with more than kGemmTileM tokens.
 // sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
+// With a row map (perm, and for GEMM 2 gate_perm) the gather / combine passes are folded in:
+// GEMM 1 then reads row r from x[perm[r]] (x_perm = x in token order), GEMM 2 writes
+// bf16(gate_perm[r] * result row r) to y[perm[r]] (y_perm = y in token order).
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st, const LaunchEvents *ev = nullptr);
+                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st, const LaunchEvents *ev = nullptr);
+                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
+                     const float *gate_perm = nullptr);
 // Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,

@@ -154,7 +154,8 @@ __global__ __launch_bounds__(1024) void sort_scan(int32_t *__restrict__ block_hi
 
 __global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids, int T, int E,
                                                 const int32_t *__restrict__ block_base,
-                                                int32_t *__restrict__ perm, int32_t *__restrict__ inv)
+                                                int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+                                                const float *__restrict__ alpha, float *__restrict__ gate_perm)
 {
     __shared__ int next_row[kMaxE];
     const int lane = threadIdx.x;
@@ -179,6 +180,7 @@ __global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids,
             const int row = next_row[k] + ahead;
             perm[row] = t;
             inv[t] = row;
+            if (alpha) gate_perm[row] = alpha[t];
         }
         __syncthreads();               // every lane has read next_row before anyone advances it
         if (live && (same & below) == 0) next_row[k] += __popcll(same);
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ x, 
 
 int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32_t *offsets,
                 int32_t *block_hist, int32_t *perm, int32_t *inv, const LayerTable *tbl, TileDesc *tiles,
-                int32_t max_tiles, hipStream_t st)
+                int32_t max_tiles, hipStream_t st, const float *alpha, float *gate_perm)
 {
     const int n_chunks = (T + kChunk - 1) / kChunk;
     hipLaunchKernelGGL(sort_hist, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist);
@@ -211,7 +213,8 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
     none.n = 0;
     hipLaunchKernelGGL(sort_scan, dim3(1), dim3(1024), 0, st, block_hist, n_chunks, E, T, counts, offsets,
                        tbl ? *tbl : none, tiles, max_tiles);
-    hipLaunchKernelGGL(sort_rank, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist, perm, inv);
+    hipLaunchKernelGGL(sort_rank, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist, perm, inv, alpha,
+                       alpha ? gate_perm : nullptr);
     return (int)hipGetLastError();
 }
 

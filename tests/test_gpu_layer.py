@@ -12,10 +12,11 @@ from workloads import WORKLOADS, Workload, f32_to_bf16_bits
 pytestmark = pytest.mark.gpu
 
 
-def run_and_check(wl, reps=1, T_of=None, check_plan=True):
+def run_and_check(wl, reps=1, T_of=None, check_plan=True, fused=False):
     """Runs all layers `reps` times through sida_run_layers and checks every layer's y, its sort
     outputs and its plan against the oracle."""
     r = make_runner(wl)
+    r.ctx.set_fusion(fused)
     st = oracle.PoolState(wl.E, wl.S)
     worst = 0.0
     for rep in range(reps):
