@@ -52,6 +52,10 @@ def _lib():
         lib.sida_oracle_moe_forward.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        lib.sida_oracle_moe_forward_topk.restype = ctypes.c_int
+        lib.sida_oracle_moe_forward_topk.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         lib.sida_oracle_threads.restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -83,6 +87,30 @@ def moe_forward(x_bf16, ids, alpha, blocks, d_model: int, d_ff: int) -> np.ndarr
     rc = _lib().sida_oracle_moe_forward(x.ctypes.data, ids.ctypes.data, alpha.ctypes.data,
                                         ctypes.cast(ptrs, ctypes.c_void_p), E, T, d_model, d_ff,
                                         y.ctypes.data)
+    if rc != 0:
+        raise ValueError("expert id out of range")
+    return y
+
+
+def moe_forward_topk(x_bf16, ids, alpha, blocks, d_model: int, d_ff: int) -> np.ndarray:
+    """y[t] = sum_j alpha[t,j] * W_out[e] relu(W_in[e] x[t]),  e = ids[t,j]   (Eq. 1, |I| = k).
+
+    ids: int32 [T,k].  alpha: float32 [T,k].  Otherwise as moe_forward.  Returns float32 [T, d]."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    alpha = np.ascontiguousarray(alpha, dtype=np.float32)
+    assert ids.ndim == 2 and alpha.shape == ids.shape
+    T, k = ids.shape
+    assert x.shape == (T, d_model)
+    keep = [np.ascontiguousarray(b, dtype=np.uint16).reshape(-1) for b in blocks]
+    for b in keep:
+        assert b.size == 2 * d_model * d_ff
+    E = len(keep)
+    ptrs = (ctypes.c_void_p * max(E, 1))(*[b.ctypes.data for b in keep])
+    y = np.empty((T, d_model), dtype=np.float32)
+    rc = _lib().sida_oracle_moe_forward_topk(x.ctypes.data, ids.ctypes.data, alpha.ctypes.data,
+                                             ctypes.cast(ptrs, ctypes.c_void_p), E, T, k, d_model, d_ff,
+                                             y.ctypes.data)
     if rc != 0:
         raise ValueError("expert id out of range")
     return y
