@@ -217,11 +217,24 @@ int sida_moe_layer_forward(sida_ctx *ctx, const sida_plan *plan, const void *x_d
                            void *workspace_dev, size_t workspace_bytes, void *compute_stream,
                            void *copy_stream);
 
+/* Experts per token, 1..SIDA_MAX_TOP_K (default 1 = Switch routing).  Eq. 1 of Section 2.1 with a
+ * selected set of k experts: y[t,:] = sum_{j<k} alpha[t,j] * f_{ids[t,j]}(x[t,:]); the paper
+ * evaluates with the hash function's top-3 experts on two of its datasets (Section 4.1).
+ * With k > 1 every "T" of the plan, forward and stage calls counts (token, expert) PAIRS:
+ * ids and alpha are [tokens, k] row-major (T = tokens*k entries, T <= max_T, T % k == 0,
+ * SIDA_EINVAL otherwise), x and y keep one row per token (T/k rows).  The pairs are sorted and
+ * run through the grouped FFN like tokens; the combine adds a token's k rows in fp32 in the order
+ * j = 0..k-1 and rounds once.  A token may name the same expert more than once.
+ * May be changed between layer calls; plans made before stay valid (they only count ids). */
+#define SIDA_MAX_TOP_K 8
+int sida_set_top_k(sida_ctx *ctx, int32_t k);
+
 /* Folds the permute-gather into the first GEMM's token-row loads (rows are read from x through
  * the sort's index, x_perm is never written) and the gate-weighted scatter-combine into the second
  * GEMM's result stores (with top-1 routing every y row is written exactly once, by the tile that
  * holds its token; y_perm is never written).  Same arithmetic, bit-identical y; two launches and
- * about two thirds of the dispatch/combine HBM traffic less per layer.  Affects
+ * about two thirds of the dispatch/combine HBM traffic less per layer.  With more than one expert
+ * per token only the gather is folded in (a y row is then a sum over several tiles).  Affects
  * sida_moe_layer_forward / sida_run_layers only; the single-stage calls keep the separate passes.
  * Off by default.  May be switched between layer calls. */
 int sida_set_fusion(sida_ctx *ctx, int32_t on);

@@ -75,6 +75,7 @@ def lib():
         "sida_moe_plan_lookahead": (C.c_int, [vp, i32, vp, i32, vp, C.c_int64, C.POINTER(SidaPlan)]),
         "sida_set_policy": (C.c_int, [vp, i32, i32]),
         "sida_set_fusion": (C.c_int, [vp, i32]),
+        "sida_set_top_k": (C.c_int, [vp, i32]),
         "sida_queue_push": (C.c_int, [vp, C.c_int64, vp, i32]),
         "sida_queue_close": (C.c_int, [vp]),
         "sida_queue_size": (C.c_int, [vp]),
@@ -189,6 +190,9 @@ class Context:
                                                _ptr(future_keys) if n else 0, n, C.byref(plan)),
                  "sida_moe_plan_lookahead")
         return plan
+
+    def set_top_k(self, k: int):
+        self._ck(lib().sida_set_top_k(self._h, k), "sida_set_top_k")
 
     def set_fusion(self, on: bool):
         self._ck(lib().sida_set_fusion(self._h, 1 if on else 0), "sida_set_fusion")

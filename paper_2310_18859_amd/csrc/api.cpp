@@ -236,7 +236,7 @@ int launch_dispatch(sida_ctx *c, const void *x, const int32_t *ids, int32_t T, c
     }
     if (!alpha) {
         TimedKernel tk(c, SIDA_K_GATHER);
-        HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st, tk.get()));
+        HIP_TRY(c, (hipError_t)launch_gather(x, ws.perm, T, c->cfg.d_model, ws.x_perm, st, tk.get(), c->top_k));
     }
     return SIDA_OK;
 }
@@ -257,7 +257,7 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
         TimedKernel tk(c, SIDA_K_GEMM1);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(x ? x : ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
-                                                x ? ws.perm : nullptr));
+                                                x ? ws.perm : nullptr, c->top_k));
     }
     {
         TimedKernel tk(c, SIDA_K_GEMM2);
@@ -281,6 +281,7 @@ int check_layer_args(const sida_ctx *c, const LayerArgs &a)
     int rc = check_plan(c, a.plan);
     if (rc) return rc;
     if (a.plan->T > 0 && (!a.x || !a.ids || !a.alpha || !a.y)) return SIDA_EINVAL;
+    if (a.plan->T % c->top_k) return SIDA_EINVAL;               // k (token, expert) pairs per token
     return SIDA_OK;
 }
 
@@ -346,15 +347,18 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
             }
             const int ring = g % kEventRing;
             if (c->ready_recorded[ring]) HIP_TRY(c, hipStreamWaitEvent(compute, c->ev_ready[ring], 0));
-            rc = launch_wave_ffn(c, sched, w, ws, compute, fused ? a.x : nullptr, fused ? a.y : nullptr);
+            // with several experts per token a y row is a sum over tiles: only the gather is folded in
+            rc = launch_wave_ffn(c, sched, w, ws, compute, fused ? a.x : nullptr,
+                                 fused && c->top_k == 1 ? a.y : nullptr);
             if (rc) return rc;
             if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_done[ring]));
             HIP_TRY(c, hipEventRecord(c->ev_done[ring], compute));
             c->forwarded_upto = g + 1;
         }
-        if (!fused) {
+        if (!fused || c->top_k > 1) {
             TimedKernel tk(c, SIDA_K_COMBINE);
-            HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute, tk.get()));
+            HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, a.alpha, p->T, c->cfg.d_model, a.y, compute, tk.get(),
+                                                  c->top_k));
         }
     }
     return SIDA_OK;
@@ -511,6 +515,13 @@ int sida_moe_plan_lookahead(sida_ctx *c, int32_t layer, const int32_t *ids_host,
     } catch (const std::bad_alloc &) {
         return SIDA_ENOMEM;
     }
+}
+
+int sida_set_top_k(sida_ctx *c, int32_t k)
+{
+    if (!c || k < 1 || k > SIDA_MAX_TOP_K) return SIDA_EINVAL;
+    c->top_k = k;
+    return SIDA_OK;
 }
 
 int sida_set_fusion(sida_ctx *c, int32_t on)
@@ -670,7 +681,7 @@ int sida_run_layers(sida_ctx *c, int32_t n, const sida_plan *const *plans, const
 int sida_dispatch(sida_ctx *c, const void *x_dev, const int32_t *ids_dev, int32_t T, void *workspace_dev,
                   size_t workspace_bytes, void *stream)
 {
-    if (!c || T < 0 || T > c->cfg.max_T) return SIDA_EINVAL;
+    if (!c || T < 0 || T > c->cfg.max_T || T % c->top_k) return SIDA_EINVAL;
     if (T == 0) return SIDA_OK;
     if (!x_dev || !ids_dev) return SIDA_EINVAL;
     int rc = check_ws(c, T, workspace_dev, workspace_bytes);
@@ -698,7 +709,7 @@ int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *wor
 int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, void *workspace_dev,
                  size_t workspace_bytes, void *stream)
 {
-    if (!c || T < 0 || T > c->cfg.max_T) return SIDA_EINVAL;
+    if (!c || T < 0 || T > c->cfg.max_T || T % c->top_k) return SIDA_EINVAL;
     if (T == 0) return SIDA_OK;
     if (!alpha_dev || !y_dev) return SIDA_EINVAL;
     int rc = check_ws(c, T, workspace_dev, workspace_bytes);
@@ -706,7 +717,7 @@ int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, vo
     const Ws ws = carve(c->cfg, T, workspace_dev);
     hipStream_t st = static_cast<hipStream_t>(stream);
     TimedKernel tk(c, SIDA_K_COMBINE);
-    HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st, tk.get()));
+    HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st, tk.get(), c->top_k));
     return SIDA_OK;
 }
 

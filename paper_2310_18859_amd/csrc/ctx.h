@@ -64,6 +64,7 @@ struct sida_ctx {
     bool events_made = false;
 
     bool fused = false;                // gather / combine folded into the grouped GEMMs
+    int32_t top_k = 1;                 // experts per token (rows of a layer call = tokens * top_k)
 
     // kernel timing
     bool profiling = false;

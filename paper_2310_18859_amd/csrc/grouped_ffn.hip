@@ -131,7 +131,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                                                                int m_tiles, int m_tall, int nw, int N, int K,
                                                                char *__restrict__ sink,
                                                                const int32_t *__restrict__ perm,
-                                                               const float *__restrict__ gate_perm)
+                                                               const float *__restrict__ gate_perm, int top_k)
 {
     constexpr int NW = WM * WN;
     constexpr int kRowBytes = BK * 2;                         // a tile row in LDS: BK bf16 (128 or 64 bytes)
@@ -192,7 +192,11 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         for (int j = 0; j < LOADS; ++j) {
             const int r = (wv * LOADS + j) * RPL + sub_row;   // row in the stage
             const int ra = min(r, c.rows - 1);                // rows past the end re-read the last one
-            const int src = FUSE == kGather ? reinterpret_cast<const int *>(side)[ra] : c.row0 + ra;
+            int src = c.row0 + ra;
+            if (FUSE == kGather) {                            // row ra of the tile is one of token src / top_k
+                src = reinterpret_cast<const int *>(side)[ra];
+                if (top_k != 1) src /= top_k;
+            }
             p[j] = r < BM ? reinterpret_cast<const char *>(A) + (size_t)src * K * 2 + piece * 16
                           : Wt + (size_t)(r - BM) * K * 2 + piece * 16;
         }
@@ -389,7 +393,7 @@ int persistent_grid()
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU, int FUSE>
 int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
               int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
-              hipStream_t st, const LaunchEvents *ev)
+              int top_k, hipStream_t st, const LaunchEvents *ev)
 {
     constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2 + (FUSE == kPlain ? 0 : WM * WN * 512);
     static_assert(kLdsBytes <= 160 * 1024, "LDS");
@@ -414,7 +418,7 @@ int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, siz
     const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
     hipExtLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU, FUSE>), dim3(grid), dim3(WM * WN * 64), kLdsBytes,
                           st, ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, (const __bf16 *)A, (__bf16 *)C, pool,
-                          expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink, perm, gate_perm);
+                          expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink, perm, gate_perm, top_k);
     return (int)hipGetLastError();
 }
 
@@ -422,43 +426,44 @@ int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, siz
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU>
 int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
            int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
-           hipStream_t st, const LaunchEvents *ev)
+           int top_k, hipStream_t st, const LaunchEvents *ev)
 {
     if (!perm)
         return launch_as<BM, BN, BK, WM, WN, STAGES, RELU, kPlain>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N,
-                                                                   K, sink, nullptr, nullptr, st, ev);
+                                                                   K, sink, nullptr, nullptr, 1, st, ev);
     return launch_as<BM, BN, BK, WM, WN, STAGES, RELU, RELU ? kGather : kScatter>(A, C, pool, expert_bytes, w_off, tiles,
                                                                                   m_tiles, m_tall, N, K, sink, perm,
-                                                                                  gate_perm, st, ev);
+                                                                                  gate_perm, top_k, st, ev);
 }
 
 }  // namespace
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev, const int32_t *perm)
+                     const LaunchEvents *ev, const int32_t *perm, int32_t top_k)
 {
     const float *gate_perm = nullptr;
     // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
     // Switch shape, other widths fall back to 128
     if (F % 256 == 0 && d >= KB1 * (ST1 - 1))
-        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
+        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
     if (F % 256 == 0 && d >= 128)
-        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
+        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
     if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
-        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
-    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, st, ev);
+        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
+    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
                      const LaunchEvents *ev, const int32_t *perm, const float *gate_perm)
 {
+    const int top_k = 1;                                     // scattering is only defined for one expert per token
     if (F < KB2 * (ST2 - 1))
         return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                                m_tall, d, F, sink, perm, gate_perm, st, ev);
+                                                m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
     return launch<128, 128, KB2, 2, 4, ST2, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                            m_tall, d, F, sink, perm, gate_perm, st, ev);
+                                            m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------

@@ -37,19 +37,20 @@ struct LaunchEvents {
 int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32_t *offsets,
                 int32_t *block_hist, int32_t *perm, int32_t *inv, const LayerTable *tbl, TileDesc *tiles,
                 int32_t max_tiles, hipStream_t st, const float *alpha = nullptr, float *gate_perm = nullptr);
-// K-a: x_perm[r,:] = x[perm[r],:], rows of d bf16 values.
+// K-a: x_perm[r,:] = x[perm[r] / k,:], rows of d bf16 values; T = rows of x_perm (k per token).
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st,
-                  const LaunchEvents *ev = nullptr);
+                  const LaunchEvents *ev = nullptr, int32_t k = 1);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
 // tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles); the
 // first m_tall of them belong to experts with more than kGemmTileM tokens.
 // sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
 // With a row map (perm, and for GEMM 2 gate_perm) the gather / combine passes are folded in:
-// GEMM 1 then reads row r from x[perm[r]] (x_perm = x in token order), GEMM 2 writes
+// GEMM 1 then reads row r from x[perm[r] / k] (x_perm = x in token order, k rows per token), GEMM 2 writes
 // bf16(gate_perm[r] * result row r) to y[perm[r]] (y_perm = y in token order).
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr);
+                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
+                     int32_t k = 1);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
@@ -58,9 +59,9 @@ int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t exper
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
                        hipStream_t st);
-// K-c: y[t,:] = alpha[t] * y_perm[inv[t],:].
+// K-c: y[t,:] = sum_{j<k} alpha[t*k+j] * y_perm[inv[t*k+j],:]; T = rows of y_perm (k per token).
 int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, int32_t T, int32_t d,
-                   void *y, hipStream_t st, const LaunchEvents *ev = nullptr);
+                   void *y, hipStream_t st, const LaunchEvents *ev = nullptr, int32_t k = 1);
 
 constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)

@@ -190,12 +190,12 @@ __global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids,
 
 // One wavefront per output row; d*2 bytes per row moved as 16-byte pieces.
 __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ x, const int32_t *__restrict__ perm,
-                                                   int T, int vec_per_row, uint4 *__restrict__ x_perm)
+                                                   int T, int vec_per_row, uint4 *__restrict__ x_perm, int k)
 {
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= T) return;
     const int lane = threadIdx.x & 63;
-    const int t = perm[r];
+    const int t = k == 1 ? perm[r] : perm[r] / k;             // row r belongs to token perm[r] / k
     const uint4 *src = x + (size_t)t * vec_per_row;
     uint4 *dst = x_perm + (size_t)r * vec_per_row;
     for (int i = lane; i < vec_per_row; i += 64) dst[i] = src[i];
@@ -219,11 +219,11 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
 }
 
 int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void *x_perm, hipStream_t st,
-                  const LaunchEvents *ev)
+                  const LaunchEvents *ev, int32_t k)
 {
     const int vec_per_row = d / 8;
     hipExtLaunchKernelGGL(gather_rows, dim3((T + 3) / 4), dim3(256), 0, st, ev ? ev->start : nullptr,
-                          ev ? ev->stop : nullptr, 0, (const uint4 *)x, perm, T, vec_per_row, (uint4 *)x_perm);
+                          ev ? ev->stop : nullptr, 0, (const uint4 *)x, perm, T, vec_per_row, (uint4 *)x_perm, k);
     return (int)hipGetLastError();
 }
 
