@@ -379,17 +379,9 @@ int persistent_grid()
     return cus;
 }
 
-// K step and ring depth of the two main shapes.  Measured on the Switch-base-128 workload: a K
-// step of 32 with a deeper ring (more bytes in flight, 64-byte row segments) is slower, and a
-// fifth stage for the 128 x 128 shape changes nothing.
-#ifndef KB1
-#define KB1 64
-#define ST1 3
-#endif
-#ifndef KB2
-#define KB2 64
-#define ST2 4
-#endif
+// Measured on the Switch-base-128 workload: a K step of 32 with a deeper ring (more bytes in
+// flight, 64-byte row segments) is slower than 64, and a fifth stage for 128 x 128 tiles changes
+// nothing.
 template <int BM, int BN, int BK, int WM, int WN, int STAGES, bool RELU, int FUSE>
 int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
               int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
@@ -436,6 +428,17 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
                                                                                   gate_perm, top_k, st, ev);
 }
 
+// Tile width of a launch: the shape whose busiest compute unit moves the fewest tile bytes through
+// its LDS, rounds of tiles times rows per K-step; a tie goes to the wide tile, which re-reads the
+// token rows half as often.
+bool wide_tiles_pay(int32_t m_tiles, int32_t N)
+{
+    const int64_t cus = persistent_grid();
+    const int64_t narrow = ((int64_t)m_tiles * (N / 128) + cus - 1) / cus * (128 + 128);
+    const int64_t wide = ((int64_t)m_tiles * (N / 256) + cus - 1) / cus * (128 + 256);
+    return wide <= narrow;
+}
+
 }  // namespace
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
@@ -443,13 +446,11 @@ int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t exper
                      const LaunchEvents *ev, const int32_t *perm, int32_t top_k)
 {
     const float *gate_perm = nullptr;
-    // wide tiles move fewer bytes per flop through LDS and L1; F is a multiple of 256 for every
-    // Switch shape, other widths fall back to 128
-    if (F % 256 == 0 && d >= KB1 * (ST1 - 1))
-        return launch<128, 256, KB1, 2, 4, ST1, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
-    if (F % 256 == 0 && d >= 128)
+    // F and d are multiples of 256 for every Switch shape; other widths fall back to 128-wide tiles.
+    // A tile's K loop needs at least STAGES-1 steps of 64.
+    if (F % 256 == 0 && d >= 128 && wide_tiles_pay(m_tiles, F))
         return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
-    if (d < 192)    // a tile's K loop needs at least STAGES-1 steps of 64
+    if (d < 192)
         return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
     return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
 }
@@ -459,11 +460,12 @@ int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t exper
                      const LaunchEvents *ev, const int32_t *perm, const float *gate_perm)
 {
     const int top_k = 1;                                     // scattering is only defined for one expert per token
-    if (F < KB2 * (ST2 - 1))
-        return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                                m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
-    return launch<128, 128, KB2, 2, 4, ST2, false>(h, y_perm, pool, expert_bytes, (size_t)F * (size_t)d * 2, tiles, m_tiles,
-                                            m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
+    const size_t w_out = (size_t)F * (size_t)d * 2;          // W_out follows W_in in an expert's block
+    if (d % 256 == 0 && wide_tiles_pay(m_tiles, d))
+        return launch<128, 256, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
+    if (F < 192)
+        return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
+    return launch<128, 128, 64, 2, 4, 4, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------
