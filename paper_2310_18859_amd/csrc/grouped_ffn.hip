@@ -83,8 +83,27 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_t
     const int sym = rounds * 8 * per_group;
     if (t < sym) {
         const int xcd = t & 7, local = t >> 3;
-        const int group = (local / per_group) * 8 + xcd;
-        const int r = local % per_group;
+        // The order the XCD walks its tiles in: blocks of its many-token groups (rounds 0 .. n_many-1,
+        // whose tiles hit in L2) alternate with equally long runs of its few-token groups (the
+        // other rounds, whose weights come from HBM), and odd XCDs start with the other kind - so
+        // that at any time about half of the compute units stream weights from HBM while the other
+        // half works out of L2, instead of the whole chip doing first one and then the other.
+        const int chunk = 4 * nw;                             // one block of a many-token group; divides per_group
+        const int n_many = (m_tall / 4) / 8, n_few = rounds - n_many;
+        const int pairs = (n_many < n_few ? n_many : n_few) * (per_group / chunk);   // chunks of the shorter kind
+        const int ci = local / chunk;
+        int pos;                                              // position in the XCD's list of one kind
+        bool few;
+        if (ci < 2 * pairs) {
+            few = (ci + xcd) & 1;
+            pos = (ci >> 1) * chunk + local % chunk;
+        } else {
+            few = n_many <= n_few;
+            pos = local - pairs * chunk;
+        }
+        const int round = (few ? n_many : 0) + pos / per_group;
+        const int group = round * 8 + xcd;
+        const int r = pos % per_group;
         const int first = group * 4;
         if (first + 4 <= m_tall) {                            // inside many-token experts: 4 x nw blocks
             const int rr = r % (4 * nw);
