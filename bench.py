@@ -46,18 +46,6 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_work(wl, plans_tokens):
-    """Per-token algorithmic bytes / flops of each kernel class ('Roofline accounting')."""
-    d, F = wl.d_model, wl.d_ff
-    return {
-        "sort": 4 * 2 + 8,                 # ids read by two passes, perm + inv written
-        "gather": 4 + 2 * d + 2 * d,       # perm, x row in, x_perm row out
-        "combine": 4 + 4 + 2 * d + 2 * d,  # inv, alpha, y_perm row in, y row out
-        "gemm1_flops": 2 * d * F,
-        "gemm2_flops": 2 * d * F,
-    }
-
-
 def time_steps(r, wl, dev, ids_host, steps, warmup, reset_each_step=False):
     import torch
     xs, idss, alphas, ys = ([d[i] for d in dev] for i in range(4))

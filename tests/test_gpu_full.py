@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
 (sida_run_layers over all layers, pool and wave sizes of the workload): integer results of every
 layer bit-exact against numpy's stable sort (which the oracle is pinned to), plans against the
 oracle's planner, and y on sampled tokens against the oracle (a token's output does not depend on
