@@ -188,6 +188,133 @@ __global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids,
     }
 }
 
+// The whole sort in one workgroup for layer calls of at most kSmallT tokens (one or two sequences
+// per batch, the paper's serving regime): wavefront w owns chunk w, the per-chunk histograms and
+// bases live in LDS, and the three launches above shrink to one.  Same results.
+constexpr int kSmallChunks = 8;
+constexpr int kSmallT = kSmallChunks * kChunk;
+
+__global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *__restrict__ ids, int T, int E,
+                                                                int32_t *__restrict__ counts,
+                                                                int32_t *__restrict__ offsets,
+                                                                int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+                                                                const float *__restrict__ alpha,
+                                                                float *__restrict__ gate_perm, const LayerTable tbl,
+                                                                TileDesc *__restrict__ tiles, int max_tiles)
+{
+    __shared__ int hist[kSmallChunks][kMaxE];      // per-chunk histogram, then first output row of (chunk, expert)
+    __shared__ int s_off[kMaxE + 1];
+    __shared__ int s_wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    for (int i = tid; i < kSmallChunks * kMaxE; i += kSmallChunks * 64) (&hist[0][0])[i] = 0;
+    __syncthreads();
+
+    int my_id[kChunk / 64];
+#pragma unroll
+    for (int r = 0; r < kChunk / 64; ++r) {
+        const int t = wv * kChunk + r * 64 + lane;
+        my_id[r] = t < T ? clamp_id(ids[t], E) : -1;
+        if (my_id[r] >= 0) atomicAdd(&hist[wv][my_id[r]], 1);
+    }
+    __syncthreads();
+
+    // expert totals -> offsets (threads 0..255: one expert each), then the bases of every chunk
+    int total = 0, incl = 0;
+    if (tid < 256) {
+        if (tid < E)
+            for (int c = 0; c < kSmallChunks; ++c) total += hist[c][tid];
+        incl = total;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) s_wsum[wv] = incl;
+    }
+    __syncthreads();
+    if (tid < 256) {
+        for (int i = 0; i < wv; ++i) incl += s_wsum[i];
+        const int excl = incl - total;
+        if (tid < E) {
+            counts[tid] = total;
+            offsets[tid] = excl;
+            s_off[tid] = excl;
+            if (tid == E - 1) {
+                offsets[E] = T;
+                s_off[E] = T;
+            }
+            int run = excl;
+            for (int c = 0; c < kSmallChunks; ++c) {
+                const int v = hist[c][tid];
+                hist[c][tid] = run;
+                run += v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // token tiles of the grouped FFN (as in sort_scan)
+    if (tbl.n > 0) {
+        int ex = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
+        if (tid < tbl.n) {
+            ex = tbl.expert[tid];
+            slot = tbl.slot[tid];
+            off = s_off[ex];
+            cnt = s_off[ex + 1] - off;
+            n_t = (cnt + kGemmTileM - 1) / kGemmTileM;
+        }
+        int inc2 = n_t;
+        if (tid < 256) {
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(inc2, o, 64);
+                if (lane >= o) inc2 += v;
+            }
+        }
+        __syncthreads();                                        // s_wsum is reused
+        if (tid < 256 && lane == 63) s_wsum[wv] = inc2;
+        __syncthreads();
+        if (tid < 256) {
+            for (int i = 0; i < wv; ++i) inc2 += s_wsum[i];
+            int at = inc2 - n_t;
+            for (int k = 0; k < n_t && at < max_tiles; ++k, ++at) {
+                TileDesc td;
+                td.slot = slot;
+                td.row0 = off + k * kGemmTileM;
+                td.rows = min(kGemmTileM, cnt - k * kGemmTileM);
+                td.expert = ex;
+                tiles[at] = td;
+            }
+        }
+    }
+
+    // ranks: wavefront w walks its chunk in rounds of 64 tokens (LDS accesses of one wavefront
+    // execute in program order, so the reads of a round precede its updates)
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < kChunk / 64; ++r) {
+        const int t = wv * kChunk + r * 64 + lane;
+        const bool live = my_id[r] >= 0;
+        const int k = live ? my_id[r] : 0;
+        unsigned long long same = __ballot(live);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const unsigned long long b = __ballot((k >> bit) & 1);
+            same &= ((k >> bit) & 1) ? b : ~b;
+        }
+        int row = 0;
+        if (live) row = hist[wv][k] + __popcll(same & below);
+        __builtin_amdgcn_wave_barrier();
+        if (live && (same & below) == 0) hist[wv][k] += __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+        if (live) {
+            perm[row] = t;
+            inv[t] = row;
+            if (alpha) gate_perm[row] = alpha[t];
+        }
+    }
+}
+
 // One wavefront per output row; d*2 bytes per row moved as 16-byte pieces.
 __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ x, const int32_t *__restrict__ perm,
                                                    int T, int vec_per_row, uint4 *__restrict__ x_perm, int k)
@@ -208,9 +335,14 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
                 int32_t max_tiles, hipStream_t st, const float *alpha, float *gate_perm)
 {
     const int n_chunks = (T + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(sort_hist, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist);
     LayerTable none;
     none.n = 0;
+    if (T <= kSmallT) {
+        hipLaunchKernelGGL(sort_small, dim3(1), dim3(kSmallChunks * 64), 0, st, ids, T, E, counts, offsets, perm, inv,
+                           alpha, alpha ? gate_perm : nullptr, tbl ? *tbl : none, tiles, max_tiles);
+        return (int)hipGetLastError();
+    }
+    hipLaunchKernelGGL(sort_hist, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist);
     hipLaunchKernelGGL(sort_scan, dim3(1), dim3(1024), 0, st, block_hist, n_chunks, E, T, counts, offsets,
                        tbl ? *tbl : none, tiles, max_tiles);
     hipLaunchKernelGGL(sort_rank, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist, perm, inv, alpha,
