@@ -133,9 +133,32 @@ int sida_workspace_layout(const sida_ctx *ctx, int32_t T, sida_ws_layout *out);
  * kept alive while the context uses it. */
 int sida_bind_pool(sida_ctx *ctx, void *pool_dev, size_t bytes);
 /* host_blocks: host array of L*E pointers, entry layer*E+e -> that expert's block in PINNED host
- * memory (pageable memory works but makes the copies synchronous).  The pointer table is copied;
+ * memory (pageable memory works but makes the copies synchronous and rules out the copy kernel).  The pointer table is copied;
  * the blocks stay the caller's and must outlive every prefetch that reads them. */
 int sida_bind_host_weights(sida_ctx *ctx, const void *const *host_blocks);
+/* Creates the two streams a context's work is enqueued on (default priority, non-blocking with
+ * respect to the null stream), with the chip's compute units divided between them: copy_stream
+ * may use copy_cus of them (a multiple of 8, taken evenly from the XCDs; at most half), the
+ * compute stream all the others, and the grouped GEMMs size their persistent grids to the
+ * compute units of the stream they run on.  This keeps the copy kernel of SIDA_PREFETCH_KERNEL off
+ * the compute units of the GEMMs: a GEMM that shares a compute unit with workgroups waiting on
+ * host-link reads runs 2-3 x slower (measured), because vector memory returns of a compute unit
+ * come back in order.  copy_cus = 0: two plain streams.  Any other streams may be passed to the
+ * forward calls instead.  Destroy the streams after the context's work has drained. */
+int sida_streams_create(int32_t copy_cus, void **compute_stream, void **copy_stream);
+int sida_streams_destroy(void *compute_stream, void *copy_stream);
+
+/* How sida_expert_prefetch moves an expert into its slot.
+ *   SIDA_PREFETCH_COPY_ENGINE  one hipMemcpyAsync per expert (works with pageable host memory too);
+ *   SIDA_PREFETCH_KERNEL       one copy kernel per wave that reads the pinned blocks over the host
+ *                              link itself: no per-expert cost (57 GB/s against 45 GB/s measured
+ *                              with 9.4 MB experts); needs every bound block in pinned memory,
+ *                              SIDA_ESTATE otherwise (bind the weights first);
+ *   SIDA_PREFETCH_AUTO         the kernel when every bound block is pinned, else the copy engine
+ *                              (default). */
+enum { SIDA_PREFETCH_AUTO = 0, SIDA_PREFETCH_COPY_ENGINE = 1, SIDA_PREFETCH_KERNEL = 2 };
+int sida_set_prefetch_mode(sida_ctx *ctx, int32_t mode);
+
 /* Forgets every resident expert: empty pool, FIFO cursor 0, wave counter 0, new epoch (plans
  * made before the reset are stale).  The caller must have drained both streams. */
 int sida_pool_reset(sida_ctx *ctx);

@@ -75,6 +75,9 @@ def lib():
         "sida_moe_plan_lookahead": (C.c_int, [vp, i32, vp, i32, vp, C.c_int64, C.POINTER(SidaPlan)]),
         "sida_set_policy": (C.c_int, [vp, i32, i32]),
         "sida_set_fusion": (C.c_int, [vp, i32]),
+        "sida_set_prefetch_mode": (C.c_int, [vp, i32]),
+        "sida_streams_create": (C.c_int, [i32, C.POINTER(vp), C.POINTER(vp)]),
+        "sida_streams_destroy": (C.c_int, [vp, vp]),
         "sida_set_top_k": (C.c_int, [vp, i32]),
         "sida_queue_push": (C.c_int, [vp, C.c_int64, vp, i32]),
         "sida_queue_close": (C.c_int, [vp]),
@@ -114,6 +117,21 @@ def _stream(s) -> int:
     if isinstance(s, int):
         return s
     return s.cuda_stream
+
+
+def streams_create(copy_cus: int):
+    """(compute_stream, copy_stream) as raw hipStream_t values; see sida_streams_create."""
+    a, b = C.c_void_p(), C.c_void_p()
+    rc = lib().sida_streams_create(copy_cus, C.byref(a), C.byref(b))
+    if rc:
+        raise SidaError(rc, "sida_streams_create")
+    return a.value, b.value
+
+
+def streams_destroy(compute_stream: int, copy_stream: int):
+    rc = lib().sida_streams_destroy(compute_stream, copy_stream)
+    if rc:
+        raise SidaError(rc, "sida_streams_destroy")
 
 
 class Context:
@@ -190,6 +208,11 @@ class Context:
                                                _ptr(future_keys) if n else 0, n, C.byref(plan)),
                  "sida_moe_plan_lookahead")
         return plan
+
+    def set_prefetch_mode(self, mode):
+        """mode: "auto", "copy_engine" or "kernel"."""
+        m = {"auto": 0, "copy_engine": 1, "kernel": 2}.get(mode, mode)
+        self._ck(lib().sida_set_prefetch_mode(self._h, m), "sida_set_prefetch_mode")
 
     def set_top_k(self, k: int):
         self._ck(lib().sida_set_top_k(self._h, k), "sida_set_top_k")

@@ -201,13 +201,26 @@ int enqueue_prefetch(sida_ctx *c, const sida_plan *p, int32_t w, hipStream_t cop
         if (dep >= 0) HIP_TRY(c, hipStreamWaitEvent(copy, c->ev_done[dep % kEventRing], 0));
         {
             Timed tm(c, SIDA_K_COPY, copy);
+            const bool by_kernel = c->prefetch_mode != SIDA_PREFETCH_COPY_ENGINE && !c->host_blocks_dev.empty();
+            CopyTable tbl;
+            tbl.n = 0;
             for (int32_t i = 0; i < p->n_active; ++i) {
                 const int32_t e = p->order[i];
                 if (p->wave[e] != g || p->hit[e] != 0) continue;
-                const void *src = c->host_blocks[(size_t)p->layer * c->cfg.E + e];
-                HIP_TRY(c, hipMemcpyAsync(c->pool + (size_t)p->slot[e] * c->expert_bytes, src, c->expert_bytes,
-                                          hipMemcpyHostToDevice, copy));
+                const size_t key = (size_t)p->layer * c->cfg.E + e;
+                char *dst = c->pool + (size_t)p->slot[e] * c->expert_bytes;
+                if (!by_kernel) {
+                    HIP_TRY(c, hipMemcpyAsync(dst, c->host_blocks[key], c->expert_bytes, hipMemcpyHostToDevice, copy));
+                    continue;
+                }
+                tbl.src[tbl.n] = c->host_blocks_dev[key];
+                tbl.dst[tbl.n] = dst;
+                if (++tbl.n == kCopyBatch) {
+                    HIP_TRY(c, (hipError_t)launch_expert_copy(tbl, c->expert_bytes, copy));
+                    tbl.n = 0;
+                }
             }
+            if (tbl.n) HIP_TRY(c, (hipError_t)launch_expert_copy(tbl, c->expert_bytes, copy));
         }
         HIP_TRY(c, hipEventRecord(c->ev_ready[ring], copy));
         c->ready_recorded[ring] = 1;
@@ -462,9 +475,75 @@ int sida_bind_host_weights(sida_ctx *c, const void *const *host_blocks)
         if (!host_blocks[i]) return SIDA_EINVAL;
     try {
         c->host_blocks.assign(host_blocks, host_blocks + n);
+        // Blocks in pinned (page-locked, device-mapped) memory can be read by a kernel; anything
+        // else is left to hipMemcpyAsync, which stages pageable memory itself.
+        c->host_blocks_dev.assign(n, nullptr);
+        bool all_pinned = true;
+        for (size_t i = 0; i < n && all_pinned; ++i) {
+            hipPointerAttribute_t at{};
+            if (hipPointerGetAttributes(&at, host_blocks[i]) != hipSuccess || at.type != hipMemoryTypeHost ||
+                !at.devicePointer) {
+                (void)hipGetLastError();                         // not an error of this call
+                all_pinned = false;
+                break;
+            }
+            c->host_blocks_dev[i] = at.devicePointer;
+        }
+        if (!all_pinned) c->host_blocks_dev.clear();
     } catch (const std::bad_alloc &) {
         return SIDA_ENOMEM;
     }
+    return SIDA_OK;
+}
+
+int sida_streams_create(int32_t copy_cus, void **compute_stream, void **copy_stream)
+{
+    if (!compute_stream || !copy_stream || copy_cus < 0) return SIDA_EINVAL;
+    *compute_stream = *copy_stream = nullptr;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SIDA_EHIP;
+    const int total = prop.multiProcessorCount;
+    if (copy_cus > 0 && (copy_cus % 8 || copy_cus > total / 2 || total > 512)) return SIDA_EINVAL;
+    hipStream_t cs = nullptr, ps = nullptr;
+    if (copy_cus == 0) {
+        if (hipStreamCreateWithFlags(&cs, hipStreamNonBlocking) != hipSuccess) return SIDA_EHIP;
+        if (hipStreamCreateWithFlags(&ps, hipStreamNonBlocking) != hipSuccess) {
+            (void)hipStreamDestroy(cs);
+            return SIDA_EHIP;
+        }
+    } else {
+        // mask bit i is compute unit i / 8 of XCD i % 8: the first copy_cus bits are copy_cus / 8
+        // compute units of every XCD
+        uint32_t copy_mask[16] = {}, comp_mask[16] = {};
+        for (int i = 0; i < total; ++i) (i < copy_cus ? copy_mask : comp_mask)[i >> 5] |= 1u << (i & 31);
+        const int words = (total + 31) / 32;
+        if (hipExtStreamCreateWithCUMask(&cs, words, comp_mask) != hipSuccess) return SIDA_EHIP;
+        if (hipExtStreamCreateWithCUMask(&ps, words, copy_mask) != hipSuccess) {
+            (void)hipStreamDestroy(cs);
+            return SIDA_EHIP;
+        }
+    }
+    *compute_stream = cs;
+    *copy_stream = ps;
+    return SIDA_OK;
+}
+
+int sida_streams_destroy(void *compute_stream, void *copy_stream)
+{
+    int rc = SIDA_OK;
+    forget_stream(static_cast<hipStream_t>(compute_stream));
+    forget_stream(static_cast<hipStream_t>(copy_stream));
+    if (compute_stream && hipStreamDestroy(static_cast<hipStream_t>(compute_stream)) != hipSuccess) rc = SIDA_EHIP;
+    if (copy_stream && hipStreamDestroy(static_cast<hipStream_t>(copy_stream)) != hipSuccess) rc = SIDA_EHIP;
+    return rc;
+}
+
+int sida_set_prefetch_mode(sida_ctx *c, int32_t mode)
+{
+    if (!c || mode < SIDA_PREFETCH_AUTO || mode > SIDA_PREFETCH_KERNEL) return SIDA_EINVAL;
+    if (mode == SIDA_PREFETCH_KERNEL && c->host_blocks_dev.empty()) return SIDA_ESTATE;
+    c->prefetch_mode = mode;
     return SIDA_OK;
 }
 

@@ -40,6 +40,8 @@ struct sida_ctx {
     char *pool = nullptr;
     size_t pool_bytes = 0;
     std::vector<const void *> host_blocks;
+    std::vector<const void *> host_blocks_dev;   // device-visible addresses of the blocks, empty if any is not pinned
+    int32_t prefetch_mode = SIDA_PREFETCH_AUTO;
 
     // residency bookkeeping (Algorithm 1 + FIFO)
     std::vector<int32_t> slot_key;     // [S] key held by each slot, -1 empty

@@ -30,6 +30,9 @@
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <unordered_map>
+
 #include "kernels.h"
 
 namespace sida {
@@ -386,15 +389,32 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     }
 }
 
-int persistent_grid()
+// Compute units the stream's kernels may run on (streams can be created with a compute-unit mask,
+// see sida_streams_create), rounded down to a multiple of the 8 XCDs; cached per stream.
+std::mutex g_cu_mu;
+std::unordered_map<hipStream_t, int> g_cu_cache;
+
+int persistent_grid(hipStream_t st)
 {
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-        cus = prop.multiProcessorCount > 0 ? (prop.multiProcessorCount + 7) / 8 * 8 : 256;
+    std::lock_guard<std::mutex> lk(g_cu_mu);
+    auto &cache = g_cu_cache;
+    auto it = cache.find(st);
+    if (it != cache.end()) return it->second;
+    int dev = 0, total = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        total = prop.multiProcessorCount;
+    int cus = total;
+    uint32_t mask[16] = {};
+    if (hipExtStreamGetCUMask(st, 16, mask) == hipSuccess) {
+        int bits = 0;
+        for (int i = 0; i < 16; ++i) bits += __builtin_popcount(mask[i]);
+        if (bits > 0 && bits < total) cus = bits;
+    } else {
+        (void)hipGetLastError();
     }
+    cus = cus >= 8 ? cus / 8 * 8 : 8;
+    cache[st] = cus;
     return cus;
 }
 
@@ -426,7 +446,8 @@ int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, siz
     int nw = n_tiles_n < 8 ? n_tiles_n : 8;                  // weight-row tiles per block of a many-token group
     while (n_tiles_n % nw) --nw;
     const int total = m_tiles * n_tiles_n;
-    const int grid = total < persistent_grid() ? (total + 7) / 8 * 8 : persistent_grid();   // multiple of 8 XCDs
+    const int cus = persistent_grid(st);
+    const int grid = total < cus ? (total + 7) / 8 * 8 : cus;   // multiple of 8 XCDs
     hipExtLaunchKernelGGL((grouped_gemm_nt<BM, BN, BK, WM, WN, STAGES, RELU, FUSE>), dim3(grid), dim3(WM * WN * 64), kLdsBytes,
                           st, ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, (const __bf16 *)A, (__bf16 *)C, pool,
                           expert_bytes, w_off, tiles, m_tiles, m_tall, nw, N, K, (char *)sink, perm, gate_perm, top_k);
@@ -450,15 +471,21 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
 // Tile width of a launch: the shape whose busiest compute unit moves the fewest tile bytes through
 // its LDS, rounds of tiles times rows per K-step; a tie goes to the wide tile, which re-reads the
 // token rows half as often.
-bool wide_tiles_pay(int32_t m_tiles, int32_t N)
+bool wide_tiles_pay(int32_t m_tiles, int32_t N, hipStream_t st)
 {
-    const int64_t cus = persistent_grid();
+    const int64_t cus = persistent_grid(st);
     const int64_t narrow = ((int64_t)m_tiles * (N / 128) + cus - 1) / cus * (128 + 128);
     const int64_t wide = ((int64_t)m_tiles * (N / 256) + cus - 1) / cus * (128 + 256);
     return wide <= narrow;
 }
 
 }  // namespace
+
+void forget_stream(hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(g_cu_mu);
+    g_cu_cache.erase(st);
+}
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
@@ -467,7 +494,7 @@ int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t exper
     const float *gate_perm = nullptr;
     // F and d are multiples of 256 for every Switch shape; other widths fall back to 128-wide tiles.
     // A tile's K loop needs at least STAGES-1 steps of 64.
-    if (F % 256 == 0 && d >= 128 && wide_tiles_pay(m_tiles, F))
+    if (F % 256 == 0 && d >= 128 && wide_tiles_pay(m_tiles, F, st))
         return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
     if (d < 192)
         return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
@@ -480,7 +507,7 @@ int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t exper
 {
     const int top_k = 1;                                     // scattering is only defined for one expert per token
     const size_t w_out = (size_t)F * (size_t)d * 2;          // W_out follows W_in in an expert's block
-    if (d % 256 == 0 && wide_tiles_pay(m_tiles, d))
+    if (d % 256 == 0 && wide_tiles_pay(m_tiles, d, st))
         return launch<128, 256, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
     if (F < 192)
         return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);

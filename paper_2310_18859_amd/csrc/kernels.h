@@ -55,6 +55,8 @@ int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t exper
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
                      const float *gate_perm = nullptr);
+// A stream is about to be destroyed: drop what is cached about it (its handle may be reused).
+void forget_stream(hipStream_t st);
 // Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
@@ -62,6 +64,16 @@ int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *
 // K-c: y[t,:] = sum_{j<k} alpha[t*k+j] * y_perm[inv[t*k+j],:]; T = rows of y_perm (k per token).
 int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, int32_t T, int32_t d,
                    void *y, hipStream_t st, const LaunchEvents *ev = nullptr, int32_t k = 1);
+
+// Prefetch by kernel: up to kCopyBatch experts per launch, src = pinned host block (device-visible
+// address), dst = pool slot.  expert_bytes is a multiple of 16.
+constexpr int kCopyBatch = 64;
+struct CopyTable {
+    int32_t n;
+    const void *src[kCopyBatch];
+    void *dst[kCopyBatch];
+};
+int launch_expert_copy(const CopyTable &tbl, size_t expert_bytes, hipStream_t st);
 
 constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)

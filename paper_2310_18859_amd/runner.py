@@ -6,11 +6,14 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from .binding import Context
+from .binding import Context, streams_create, streams_destroy
 
 
 class MoERunner:
-    def __init__(self, L, E, d_model, d_ff, S, W, max_T, device="cuda:0"):
+    def __init__(self, L, E, d_model, d_ff, S, W, max_T, device="cuda:0", copy_cus=None):
+        """copy_cus: compute units set aside for the copy stream (sida_streams_create).  None: 16 when
+        experts have to stream through the pool (S < L*E), else 0 (plain streams, every compute unit
+        for the GEMMs)."""
         if not torch.cuda.is_available():
             raise RuntimeError("MoERunner needs a GPU: the HIP path has no CPU fallback")
         self.dev = torch.device(device)
@@ -22,8 +25,12 @@ class MoERunner:
         self.pool = torch.zeros(S * self.expert_bytes, dtype=torch.uint8, device=self.dev)
         self.ctx.bind_pool(self.pool)
         self.workspace = torch.zeros(max(256, self.ctx.workspace_bytes(max_T)), dtype=torch.uint8, device=self.dev)
-        self.compute = torch.cuda.Stream(device=self.dev)
-        self.copy = torch.cuda.Stream(device=self.dev)
+        if copy_cus is None:
+            copy_cus = 16 if S < L * E else 0
+        self.copy_cus = copy_cus
+        self._raw_streams = streams_create(copy_cus)
+        self.compute = torch.cuda.ExternalStream(self._raw_streams[0], device=self.dev)
+        self.copy = torch.cuda.ExternalStream(self._raw_streams[1], device=self.dev)
         self.host_weights = None
         torch.cuda.synchronize(self.dev)      # the fills above ran on the default stream
 
@@ -82,3 +89,6 @@ class MoERunner:
     def close(self):
         self.sync()
         self.ctx.close()
+        if self._raw_streams is not None:
+            streams_destroy(*self._raw_streams)
+            self._raw_streams = None

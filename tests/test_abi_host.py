@@ -135,3 +135,14 @@ def test_workspace_layout_is_aligned_and_ordered():
     assert lay.h - lay.x_perm >= 4999 * 768 * 2 and lay.y_perm - lay.h >= 4999 * 3072 * 2
     assert lay.total == ctx.workspace_bytes(4999)
     assert ctx.expert_bytes() == 4 * 768 * 3072
+
+
+def test_prefetch_mode_arguments():
+    ctx = sm.Context(1, 4, 128, 128, 2, 1, 8)
+    ctx.set_prefetch_mode("auto")
+    ctx.set_prefetch_mode("copy_engine")
+    with pytest.raises(sm.SidaError) as e:                # no pinned blocks bound: the kernel cannot read them
+        ctx.set_prefetch_mode("kernel")
+    assert e.value.code == -3
+    with pytest.raises(sm.SidaError):
+        ctx.set_prefetch_mode(3)

@@ -144,3 +144,32 @@ def test_explicit_prefetch_then_forward_and_order_errors():
         r.ctx.moe_layer_forward(plans[0], *dev[0], r.workspace, r.compute, r.copy)
     assert e.value.code == -3
     r.close()
+
+
+@pytest.mark.parametrize("mode", ["copy_engine", "kernel"])
+def test_prefetch_by_copy_engine_and_by_kernel(mode):
+    say(f"prefetch mode {mode}")
+    wl = Workload(140, "prefetch-modes", 3, 9, 256, 512, 700, 1.0, 4, 2)
+    r = make_runner(wl)
+    r.ctx.set_prefetch_mode(mode)
+    worst = 0.0
+    for rep in range(2):
+        ins = [layer_inputs(wl, l) for l in range(wl.L)]
+        plans = r.plan_all([i[1] for i in ins])
+        assert sum(p.n_miss for p in plans) > wl.S                # slots are reused within the pass
+        dev = [r.to_device(*i) for i in ins]
+        r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
+        r.sync()
+        for l in range(wl.L):
+            x_bits, ids, alpha = ins[l]
+            y = bf16_tensor_to_f32(dev[l][3])
+            worst = max(worst, assert_close(y, oracle_layer(wl, r, l, x_bits, ids, alpha), f"{mode} rep {rep} layer {l}"))
+    # the pool holds exactly what the plan says, byte for byte
+    keys, _, _ = r.ctx.pool_state()
+    hw = r.host_weights.numpy()
+    pool = r.pool.view(torch.uint16).reshape(wl.S, -1).cpu().numpy()
+    for s, key in enumerate(keys):
+        if key >= 0:
+            assert np.array_equal(pool[s], hw[key]), f"slot {s}"
+    r.close()
+    say(f"  max rel err {worst:.3e}")
