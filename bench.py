@@ -183,6 +183,9 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; 0 = as defined)")
     ap.add_argument("--zipf", type=float, default=None, help="override the Zipf exponent (0 = uniform ids)")
+    ap.add_argument("--copy-cus", type=int, default=-1,
+                    help="compute units set aside for the copy stream in the streaming legs (-1: the runner's default)")
+    ap.add_argument("--prefetch", choices=["auto", "copy_engine", "kernel"], default="auto")
     ap.add_argument("--serve", choices=["off", "short", "sweep"], default="short",
                     help="stream-of-batches leg: a few pool sizes and policies (short) or the full table (sweep)")
     ap.add_argument("--serve-tokens", type=int, default=128, help="tokens per batch of the stream")
@@ -206,10 +209,11 @@ def main():
 
     # ---- streaming: the workload as stated (S-slot pool fed from pinned host memory) ----------
     log(f"[bench] workload {wl.name}: L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T} S={wl.S} W={wl.W}")
-    r = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.S, wl.W, wl.T)
+    r = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.S, wl.W, wl.T, copy_cus=None if a.copy_cus < 0 else a.copy_cus)
     t0 = time.perf_counter()
     fill_host_weights(wl, r.alloc_host_weights(), progress=lambda i, n: log(f"[bench] weights {i}/{n}"))
     log(f"[bench] host weights: {wl.L * wl.E * wl.expert_bytes / 1e9:.2f} GB pinned in {time.perf_counter() - t0:.1f} s")
+    r.ctx.set_prefetch_mode(a.prefetch)
     ins = [(gen_x(wl, l), gen_ids(wl, l), gen_gate(wl, l)) for l in range(wl.L)]
     ids_host = [i[1] for i in ins]
     dev = [r.to_device(*i) for i in ins]
@@ -243,9 +247,9 @@ def main():
         log(f"[bench] oracle: {cpu['value']:.1f} tokens/s on {cpu['cores']} threads")
 
     # ---- resident: same kernels with every expert already in HBM (pool of L*E slots) -----------
+    hw = r.host_weights
+    r.close()                                                    # also destroys its streams
     if a.only in ("both", "resident"):
-        hw = r.host_weights
-        r.close()
         r2 = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.L * wl.E, wl.E, wl.T)
         r2.host_weights = hw
         base = hw.data_ptr()

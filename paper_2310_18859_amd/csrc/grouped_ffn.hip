@@ -93,7 +93,10 @@ __device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_t
         // half works out of L2, instead of the whole chip doing first one and then the other.
         const int chunk = 4 * nw;                             // one block of a many-token group; divides per_group
         const int n_many = (m_tall / 4) / 8, n_few = rounds - n_many;
-        const int pairs = (n_many < n_few ? n_many : n_few) * (per_group / chunk);   // chunks of the shorter kind
+        // (only when an XCD has at least two rounds of either kind: on smaller launches the plain
+        // order measured faster)
+        const int shorter = n_many < n_few ? n_many : n_few;
+        const int pairs = shorter >= 2 ? shorter * (per_group / chunk) : 0;         // chunks of the shorter kind
         const int ci = local / chunk;
         int pos;                                              // position in the XCD's list of one kind
         bool few;

@@ -15,17 +15,21 @@ namespace sida {
 namespace {
 
 constexpr int kInFlight = 8;          // 16-byte loads in flight per lane
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void copy_experts(const CopyTable tbl, size_t vecs_per_expert)
 {
-    const uint4 *__restrict__ src = static_cast<const uint4 *>(tbl.src[blockIdx.y]);
-    uint4 *__restrict__ dst = static_cast<uint4 *>(tbl.dst[blockIdx.y]);
+    const u32x4 *__restrict__ src = static_cast<const u32x4 *>(tbl.src[blockIdx.y]);
+    u32x4 *__restrict__ dst = static_cast<u32x4 *>(tbl.dst[blockIdx.y]);
     const size_t stride = (size_t)gridDim.x * 256 * kInFlight;
     for (size_t base = (size_t)blockIdx.x * 256 * kInFlight + threadIdx.x; base < vecs_per_expert; base += stride) {
-        uint4 v[kInFlight];
+        u32x4 v[kInFlight];
 #pragma unroll
         for (int i = 0; i < kInFlight; ++i)
             if (base + (size_t)i * 256 < vecs_per_expert) v[i] = src[base + (size_t)i * 256];
+        // plain stores: a wave's experts (150 MB at the bench workload) stay in the 256 MB Infinity
+        // Cache until the wave's GEMMs read them; with non-temporal stores GEMM 1 of a wave was
+        // 40 % slower
 #pragma unroll
         for (int i = 0; i < kInFlight; ++i)
             if (base + (size_t)i * 256 < vecs_per_expert) dst[base + (size_t)i * 256] = v[i];

@@ -87,6 +87,8 @@ class MoERunner:
         torch.cuda.synchronize(self.dev)      # every stream of the device
 
     def close(self):
+        if self._raw_streams is None:
+            return
         self.sync()
         self.ctx.close()
         if self._raw_streams is not None:
