@@ -286,6 +286,13 @@ int sida_grouped_ffn(sida_ctx *ctx, const sida_plan *plan, int32_t wave, void *w
 int sida_combine(sida_ctx *ctx, const float *alpha_dev, int32_t T, void *y_dev,
                  void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* Inspection: the order in which a grouped-GEMM launch walks its output tiles.  For a launch over
+ * m_tiles token tiles (the first m_tall of them belonging to experts with more than one tile) and
+ * n_tiles_n weight-row tiles, fills token_tile[t], weight_tile[t] for t = 0 .. m_tiles*n_tiles_n-1
+ * (host arrays); output tile t runs on XCD t % 8.  Host only, no GPU: the device code uses the
+ * same function, so tests can check that the order visits every tile exactly once. */
+int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t *token_tile, int32_t *weight_tile);
+
 /* ---- kernel timing (for the benchmark's roofline figures) ----------------------------------- */
 
 enum { SIDA_K_SORT = 0, SIDA_K_GATHER = 1, SIDA_K_GEMM1 = 2, SIDA_K_GEMM2 = 3, SIDA_K_COMBINE = 4,

@@ -76,6 +76,7 @@ def lib():
         "sida_set_policy": (C.c_int, [vp, i32, i32]),
         "sida_set_fusion": (C.c_int, [vp, i32]),
         "sida_set_prefetch_mode": (C.c_int, [vp, i32]),
+        "sida_tile_order": (C.c_int, [i32, i32, i32, vp, vp]),
         "sida_streams_create": (C.c_int, [i32, C.POINTER(vp), C.POINTER(vp)]),
         "sida_streams_destroy": (C.c_int, [vp, vp]),
         "sida_set_top_k": (C.c_int, [vp, i32]),
@@ -117,6 +118,16 @@ def _stream(s) -> int:
     if isinstance(s, int):
         return s
     return s.cuda_stream
+
+
+def tile_order(m_tiles: int, m_tall: int, n_tiles_n: int):
+    """[(token tile, weight-row tile)] in the order a grouped-GEMM launch walks its output tiles."""
+    n = m_tiles * n_tiles_n
+    a, b = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
+    rc = lib().sida_tile_order(m_tiles, m_tall, n_tiles_n, a, b)
+    if rc:
+        raise SidaError(rc, "sida_tile_order")
+    return list(zip(a[:n], b[:n]))
 
 
 def streams_create(copy_cus: int):

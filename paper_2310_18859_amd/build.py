@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsida_moe.so")
 SOURCES = ["api.cpp", "plan.cpp", "sort_gather.hip", "grouped_ffn.hip", "combine.hip", "prefetch.hip"]
-HEADERS = ["ctx.h", "kernels.h"]
+HEADERS = ["ctx.h", "kernels.h", "tile_order.h"]
 
 
 def _newest_source() -> float:

@@ -8,6 +8,7 @@
 
 #include "ctx.h"
 #include "kernels.h"
+#include "tile_order.h"
 
 using namespace sida;
 
@@ -797,6 +798,20 @@ int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, vo
     hipStream_t st = static_cast<hipStream_t>(stream);
     TimedKernel tk(c, SIDA_K_COMBINE);
     HIP_TRY(c, (hipError_t)launch_combine(ws.y_perm, ws.inv, alpha_dev, T, c->cfg.d_model, y_dev, st, tk.get(), c->top_k));
+    return SIDA_OK;
+}
+
+int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t *token_tile, int32_t *weight_tile)
+{
+    if (m_tiles < 0 || m_tall < 0 || m_tall > m_tiles || n_tiles_n < 1 || !token_tile || !weight_tile) return SIDA_EINVAL;
+    if ((int64_t)m_tiles * n_tiles_n > INT32_MAX) return SIDA_EINVAL;
+    const int nw = tile_block_width(n_tiles_n);
+    for (int32_t t = 0; t < m_tiles * n_tiles_n; ++t) {
+        int mt, nt;
+        map_tile(t, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
+        token_tile[t] = mt;
+        weight_tile[t] = nt;
+    }
     return SIDA_OK;
 }
 

@@ -34,6 +34,7 @@
 #include <unordered_map>
 
 #include "kernels.h"
+#include "tile_order.h"
 
 namespace sida {
 
@@ -61,69 +62,6 @@ __device__ __forceinline__ void load_word_to_lds(const void *gsrc, void *lds_dst
 {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
                                      (__attribute__((address_space(3))) void *)lds_dst, 4, 0, 0);
-}
-
-// Output tile t of a launch -> (token tile, weight-row tile).
-//
-// What decides the speed is the number of bytes that miss the L2: every XCD has its own 4 MiB L2,
-// and whatever misses it (HBM or Infinity Cache alike) arrives at ~6.5 TB/s over all XCDs, a
-// third of the L2-hit rate.  Workgroup b runs on XCD b % 8 (round-robin dispatch) and a persistent
-// workgroup takes tiles b, b+G, b+2G, ... with G a multiple of 8, so tile t is computed on XCD
-// t % 8, and the 32 compute units of an XCD work on 32 consecutive tiles of that XCD's sequence at
-// any time.  The sequence is built from groups of 4 consecutive token tiles (the list is sorted by
-// expert, most tokens first), dealt round-robin to the XCDs:
-//  * a group inside one many-token expert is walked as 4 x nw blocks (4 token tiles x nw weight-row
-//    tiles): the 32 concurrent tiles share 4 token tiles and nw weight tiles, so the expert's
-//    weights enter this L2 once per group instead of once per token tile;
-//  * any other group (few-token experts, all with different weights) is walked token tile by token
-//    tile, so a token tile is fetched once and used by all its weight-row tiles at the same time.
-// Groups that do not fill a complete round of 8, and the last (< 4) token tiles, follow in plain
-// order.  The mapping is a bijection on [0, m_tiles * n_tiles_n).
-__device__ __forceinline__ void map_tile(int t, int m_tiles, int m_tall, int n_tiles_n, int nw, int *mt, int *nt)
-{
-    const int per_group = 4 * n_tiles_n;
-    const int rounds = (m_tiles / 4) / 8;                     // complete rounds of 8 groups
-    const int sym = rounds * 8 * per_group;
-    if (t < sym) {
-        const int xcd = t & 7, local = t >> 3;
-        // The order the XCD walks its tiles in: blocks of its many-token groups (rounds 0 .. n_many-1,
-        // whose tiles hit in L2) alternate with equally long runs of its few-token groups (the
-        // other rounds, whose weights come from HBM), and odd XCDs start with the other kind - so
-        // that at any time about half of the compute units stream weights from HBM while the other
-        // half works out of L2, instead of the whole chip doing first one and then the other.
-        const int chunk = 4 * nw;                             // one block of a many-token group; divides per_group
-        const int n_many = (m_tall / 4) / 8, n_few = rounds - n_many;
-        // (only when an XCD has at least two rounds of either kind: on smaller launches the plain
-        // order measured faster)
-        const int shorter = n_many < n_few ? n_many : n_few;
-        const int pairs = shorter >= 2 ? shorter * (per_group / chunk) : 0;         // chunks of the shorter kind
-        const int ci = local / chunk;
-        int pos;                                              // position in the XCD's list of one kind
-        bool few;
-        if (ci < 2 * pairs) {
-            few = (ci + xcd) & 1;
-            pos = (ci >> 1) * chunk + local % chunk;
-        } else {
-            few = n_many <= n_few;
-            pos = local - pairs * chunk;
-        }
-        const int round = (few ? n_many : 0) + pos / per_group;
-        const int group = round * 8 + xcd;
-        const int r = pos % per_group;
-        const int first = group * 4;
-        if (first + 4 <= m_tall) {                            // inside many-token experts: 4 x nw blocks
-            const int rr = r % (4 * nw);
-            *mt = first + rr / nw;
-            *nt = (r / (4 * nw)) * nw + rr % nw;
-        } else {
-            *mt = first + r / n_tiles_n;
-            *nt = r % n_tiles_n;
-        }
-    } else {
-        const int rest = t - sym;
-        *mt = rounds * 32 + rest / n_tiles_n;
-        *nt = rest % n_tiles_n;
-    }
 }
 
 // Persistent workgroups: one per compute unit, each walks its tiles t = b, b+G, ...
@@ -446,8 +384,7 @@ int launch_as(const void *A, void *C, const char *pool, size_t expert_bytes, siz
         return 0;
     }
     const int n_tiles_n = N / BN;
-    int nw = n_tiles_n < 8 ? n_tiles_n : 8;                  // weight-row tiles per block of a many-token group
-    while (n_tiles_n % nw) --nw;
+    const int nw = tile_block_width(n_tiles_n);
     const int total = m_tiles * n_tiles_n;
     const int cus = persistent_grid(st);
     const int grid = total < cus ? (total + 7) / 8 * 8 : cus;   // multiple of 8 XCDs

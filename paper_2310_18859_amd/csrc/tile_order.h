@@ -1,0 +1,90 @@
+// The order in which the grouped GEMMs walk the output tiles of a launch.  Plain integer code for
+// host and device: the host side serves sida_tile_order(), with which the order is checked to be
+// a bijection without a GPU.
+#pragma once
+
+#if defined(__HIPCC__) || defined(__CUDACC__)
+#define SIDA_HD __host__ __device__ __forceinline__
+#else
+#define SIDA_HD inline
+#endif
+
+namespace sida {
+
+// Output tile t of a launch -> (token tile, weight-row tile).
+//
+// What decides the speed is the number of bytes that miss the L2: every XCD has its own 4 MiB L2,
+// and whatever misses it (HBM or Infinity Cache alike) arrives at ~6.5 TB/s over all XCDs, a
+// third of the L2-hit rate.  Workgroup b runs on XCD b % 8 (round-robin dispatch) and a persistent
+// workgroup takes tiles b, b+G, b+2G, ... with G a multiple of 8, so tile t is computed on XCD
+// t % 8, and the compute units of an XCD work on consecutive tiles of that XCD's sequence at any
+// time.  The sequence is built from groups of 4 consecutive token tiles (the list is sorted by
+// expert, most tokens first), dealt round-robin to the XCDs:
+//  * a group inside one many-token expert is walked as 4 x nw blocks (4 token tiles x nw weight-row
+//    tiles): the concurrent tiles share 4 token tiles and nw weight tiles, so the expert's
+//    weights enter this L2 once per group instead of once per token tile;
+//  * any other group (few-token experts, all with different weights) is walked token tile by token
+//    tile, so a token tile is fetched once and used by all its weight-row tiles at the same time.
+// Groups that do not fill a complete round of 8, and the last (< 4) token tiles, follow in plain
+// order.  m_tall: the leading token tiles that belong to experts with more than one tile;
+// nw divides n_tiles_n.  The mapping is a bijection on [0, m_tiles * n_tiles_n).
+SIDA_HD void map_tile(int t, int m_tiles, int m_tall, int n_tiles_n, int nw, int *mt, int *nt)
+{
+    const int per_group = 4 * n_tiles_n;
+    const int rounds = (m_tiles / 4) / 8;                     // complete rounds of 8 groups
+    const int sym = rounds * 8 * per_group;
+    if (t >= sym) {
+        const int rest = t - sym;
+        *mt = rounds * 32 + rest / n_tiles_n;
+        *nt = rest % n_tiles_n;
+        return;
+    }
+    const int xcd = t & 7, local = t >> 3;                    // position in the XCD's sequence
+    // An XCD's many-token groups are rounds 0 .. n_many-1 (their tiles hit in L2), its few-token
+    // groups the other rounds (their weights come from HBM).  With at least two rounds of either
+    // kind, blocks of the one alternate with equally long runs of the other, and odd XCDs start
+    // with the other kind - so that at any time about half of the compute units stream weights
+    // from HBM while the other half works out of L2, instead of the whole chip doing first one and
+    // then the other.  On smaller launches the plain order measured faster.
+    const int n_many = (m_tall / 4) / 8, n_few = rounds - n_many;
+    const int shorter = n_many < n_few ? n_many : n_few;
+    int round, r;
+    if (shorter < 2) {
+        round = local / per_group;
+        r = local % per_group;
+    } else {
+        const int chunk = 4 * nw;                             // one block of a many-token group; divides per_group
+        const int pairs = shorter * (per_group / chunk);      // chunks of the shorter kind
+        const int ci = local / chunk;
+        int pos;                                              // position in the XCD's list of one kind
+        bool few;
+        if (ci < 2 * pairs) {
+            few = (ci + xcd) & 1;
+            pos = (ci >> 1) * chunk + local % chunk;
+        } else {                                              // what is left of the longer kind
+            few = n_many <= n_few;
+            pos = local - pairs * chunk;
+        }
+        round = (few ? n_many : 0) + pos / per_group;
+        r = pos % per_group;
+    }
+    const int first = (round * 8 + xcd) * 4;
+    if (first + 4 <= m_tall) {                                // inside many-token experts: 4 x nw blocks
+        const int rr = r % (4 * nw);
+        *mt = first + rr / nw;
+        *nt = (r / (4 * nw)) * nw + rr % nw;
+    } else {
+        *mt = first + r / n_tiles_n;
+        *nt = r % n_tiles_n;
+    }
+}
+
+// Weight-row tiles per block of a many-token group: the largest divisor of n_tiles_n up to 8.
+SIDA_HD int tile_block_width(int n_tiles_n)
+{
+    int nw = n_tiles_n < 8 ? n_tiles_n : 8;
+    while (n_tiles_n % nw) --nw;
+    return nw;
+}
+
+}  // namespace sida

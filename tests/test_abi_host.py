@@ -146,3 +146,25 @@ def test_prefetch_mode_arguments():
     assert e.value.code == -3
     with pytest.raises(sm.SidaError):
         ctx.set_prefetch_mode(3)
+
+
+def test_tile_order_visits_every_tile_once():
+    """The walk order of a grouped-GEMM launch (the same function the kernels use) is a bijection for
+    every mix of many-token and few-token tiles, including the launches whose XCDs alternate the two."""
+    rng = np.random.default_rng(5)
+    shapes = [(m, mt, n) for m in (0, 1, 3, 4, 31, 32, 33, 63, 64, 65, 100, 204, 257, 330, 512)
+              for mt in sorted({0, 2 if m >= 2 else 0, m // 3, m // 2, m - m % 4, m}) if mt <= m
+              for n in (1, 3, 4, 6, 12, 16, 24)]
+    shapes += [(int(rng.integers(1, 700)), 0, int(rng.choice([3, 6, 12, 16, 32]))) for _ in range(40)]
+    for m, mt, n in shapes:
+        if mt == 0 and rng.random() < 0.5 and m > 8:
+            mt = int(rng.integers(0, m + 1))
+        order = sm.tile_order(m, mt, n)
+        assert len(order) == m * n
+        assert sorted(order) == [(a, b) for a in range(m) for b in range(n)], (m, mt, n)
+    # cases where the mixing is active: at least two rounds (64 token tiles) of either kind
+    mixed = sm.tile_order(204, 100, 12)
+    plain = [(t // 12, t % 12) for t in range(204 * 12)]
+    assert mixed != plain and sorted(mixed) == plain
+    with pytest.raises(sm.SidaError):
+        sm.tile_order(4, 5, 3)
