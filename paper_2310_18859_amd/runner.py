@@ -27,8 +27,14 @@ class MoERunner:
         self.workspace = torch.zeros(max(256, self.ctx.workspace_bytes(max_T)), dtype=torch.uint8, device=self.dev)
         if copy_cus is None:
             copy_cus = 16 if S < L * E else 0
+        try:
+            self._raw_streams = streams_create(copy_cus)
+        except Exception:                     # no compute-unit masks on this driver: plain streams
+            if copy_cus == 0:
+                raise
+            copy_cus = 0
+            self._raw_streams = streams_create(0)
         self.copy_cus = copy_cus
-        self._raw_streams = streams_create(copy_cus)
         self.compute = torch.cuda.ExternalStream(self._raw_streams[0], device=self.dev)
         self.copy = torch.cuda.ExternalStream(self._raw_streams[1], device=self.dev)
         self.host_weights = None
