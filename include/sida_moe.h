@@ -286,6 +286,39 @@ int sida_grouped_ffn(sida_ctx *ctx, const sida_plan *plan, int32_t wave, void *w
 int sida_combine(sida_ctx *ctx, const float *alpha_dev, int32_t T, void *y_dev,
                  void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* ---- the hash function of the hash-building thread (Section 3.2.2) ----------------------------
+ * Predicts the hash table of a batch from the token embeddings alone: for every token and MoE
+ * layer the top_k experts and their scaling factors.  Network: a fully connected layer that
+ * compresses the embedding to C values, a 2-layer LSTM of width C over the sequence, attention of
+ * the LSTM outputs over themselves (dot-product scores) with SparseMax weights, a residual
+ * connection adding the token's compressed embedding, and one linear head of E logits per MoE
+ * layer; alpha is the SoftMax probability of the expert within its head, the top_k largest are
+ * kept (ties to the lower expert id).  All arithmetic in fp32.  No context is needed.
+ * params_dev: device fp32, sida_hash_param_count() values packed in this order:
+ *   w_in [C, d_model], b_in [C],
+ *   LSTM layer 1: w_ih [4C, C], w_hh [4C, C], b_ih [4C], b_hh [4C]   (gate rows: input, forget, cell, output),
+ *   LSTM layer 2: the same four,
+ *   w_out [L*E, C], b_out [L*E]                                       (head l = rows l*E .. l*E+E-1).
+ * x_dev: device bf16 [n_seq * seq_len, d_model], sequences one after the other (attention and the
+ * LSTM never cross a sequence boundary).  Outputs, device: ids_dev int32 and alpha_dev fp32, both
+ * [L, n_seq * seq_len, top_k] - layer l's slice is exactly the ids / alpha array that
+ * sida_moe_plan (after a copy to the host) and sida_moe_layer_forward take (with sida_set_top_k).
+ * workspace_dev: device, 256-byte aligned, >= sida_hash_workspace_bytes(n_seq * seq_len).
+ * Limits: C is 64 or 128; E <= SIDA_MAX_E; L*E <= 8192; top_k <= min(E, SIDA_MAX_TOP_K);
+ * seq_len <= max_seq_len <= 4096.  Asynchronous on `stream`. */
+typedef struct sida_hash_config {
+    int32_t d_model;      /* embedding width                       */
+    int32_t C;            /* compressed width = LSTM hidden width  */
+    int32_t L, E;         /* MoE layers, experts per layer         */
+    int32_t top_k;        /* experts predicted per token and layer */
+    int32_t max_seq_len;  /* longest sequence                      */
+} sida_hash_config;
+size_t sida_hash_param_count(const sida_hash_config *cfg);                       /* 0 on a bad config */
+size_t sida_hash_workspace_bytes(const sida_hash_config *cfg, int32_t n_tokens); /* 0 on a bad config */
+int sida_hash_forward(const sida_hash_config *cfg, const float *params_dev, const void *x_dev, int32_t n_seq,
+                      int32_t seq_len, int32_t *ids_dev, float *alpha_dev, void *workspace_dev,
+                      size_t workspace_bytes, void *stream);
+
 /* Inspection: the order in which a grouped-GEMM launch walks its output tiles.  For a launch over
  * m_tiles token tiles (the first m_tall of them belonging to experts with more than one tile) and
  * n_tiles_n weight-row tiles, fills token_tile[t], weight_tile[t] for t = 0 .. m_tiles*n_tiles_n-1

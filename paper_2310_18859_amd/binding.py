@@ -40,6 +40,10 @@ class SidaPlan(C.Structure):
     ]
 
 
+class SidaHashConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d_model", "C", "L", "E", "top_k", "max_seq_len")]
+
+
 class WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in
                 ("counts", "offsets", "block_hist", "perm", "inv", "x_perm", "h", "y_perm", "tiles", "sink", "gate_perm", "total")]
@@ -77,6 +81,9 @@ def lib():
         "sida_set_fusion": (C.c_int, [vp, i32]),
         "sida_set_prefetch_mode": (C.c_int, [vp, i32]),
         "sida_tile_order": (C.c_int, [i32, i32, i32, vp, vp]),
+        "sida_hash_param_count": (sz, [C.POINTER(SidaHashConfig)]),
+        "sida_hash_workspace_bytes": (sz, [C.POINTER(SidaHashConfig), i32]),
+        "sida_hash_forward": (C.c_int, [C.POINTER(SidaHashConfig), vp, vp, i32, i32, vp, vp, vp, sz, vp]),
         "sida_streams_create": (C.c_int, [i32, C.POINTER(vp), C.POINTER(vp)]),
         "sida_streams_destroy": (C.c_int, [vp, vp]),
         "sida_set_top_k": (C.c_int, [vp, i32]),
@@ -128,6 +135,21 @@ def tile_order(m_tiles: int, m_tall: int, n_tiles_n: int):
     if rc:
         raise SidaError(rc, "sida_tile_order")
     return list(zip(a[:n], b[:n]))
+
+
+def hash_param_count(cfg: SidaHashConfig) -> int:
+    return lib().sida_hash_param_count(C.byref(cfg))
+
+
+def hash_workspace_bytes(cfg: SidaHashConfig, n_tokens: int) -> int:
+    return lib().sida_hash_workspace_bytes(C.byref(cfg), n_tokens)
+
+
+def hash_forward(cfg: SidaHashConfig, params, x, n_seq, seq_len, ids, alpha, workspace, stream):
+    rc = lib().sida_hash_forward(C.byref(cfg), _ptr(params), _ptr(x), n_seq, seq_len, _ptr(ids), _ptr(alpha),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc:
+        raise SidaError(rc, "sida_hash_forward")
 
 
 def streams_create(copy_cus: int):

@@ -801,6 +801,45 @@ int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, vo
     return SIDA_OK;
 }
 
+// ---- hash function ---------------------------------------------------------------------------
+namespace {
+bool hash_cfg_ok(const sida_hash_config *h)
+{
+    return h && (h->C == 64 || h->C == 128) && h->d_model >= 8 && h->d_model <= 8192 && h->L >= 1 && h->E >= 1 &&
+           h->E <= SIDA_MAX_E && (int64_t)h->L * h->E <= 8192 && h->top_k >= 1 && h->top_k <= SIDA_MAX_TOP_K &&
+           h->top_k <= h->E && h->max_seq_len >= 1 && h->max_seq_len <= 4096;
+}
+}  // namespace
+
+size_t sida_hash_param_count(const sida_hash_config *h)
+{
+    if (!hash_cfg_ok(h)) return 0;
+    const size_t C = h->C;
+    return C * h->d_model + C + 2 * (2 * 4 * C * C + 2 * 4 * C) + (size_t)h->L * h->E * C + (size_t)h->L * h->E;
+}
+
+size_t sida_hash_workspace_bytes(const sida_hash_config *h, int32_t n_tokens)
+{
+    if (!hash_cfg_ok(h) || n_tokens < 0) return 0;
+    return sizeof(float) * 8 * (size_t)h->C * (size_t)n_tokens + 256;
+}
+
+int sida_hash_forward(const sida_hash_config *h, const float *params_dev, const void *x_dev, int32_t n_seq,
+                      int32_t seq_len, int32_t *ids_dev, float *alpha_dev, void *workspace_dev, size_t workspace_bytes,
+                      void *stream)
+{
+    if (!hash_cfg_ok(h) || n_seq < 0 || seq_len < 0 || seq_len > h->max_seq_len) return SIDA_EINVAL;
+    if ((int64_t)n_seq * seq_len > INT32_MAX / 8) return SIDA_EINVAL;
+    if (n_seq == 0 || seq_len == 0) return SIDA_OK;
+    if (!params_dev || !x_dev || !ids_dev || !alpha_dev || !workspace_dev) return SIDA_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) & 255u) return SIDA_EINVAL;
+    if (workspace_bytes < sida_hash_workspace_bytes(h, n_seq * seq_len)) return SIDA_ENOSPC;
+    const HashShape sh{h->d_model, h->C, h->L, h->E, h->top_k};
+    const int rc = launch_hash_forward(sh, params_dev, x_dev, n_seq, seq_len, ids_dev, alpha_dev,
+                                       static_cast<float *>(workspace_dev), static_cast<hipStream_t>(stream));
+    return rc == 0 ? SIDA_OK : SIDA_EHIP;
+}
+
 int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t *token_tile, int32_t *weight_tile)
 {
     if (m_tiles < 0 || m_tall < 0 || m_tall > m_tiles || n_tiles_n < 1 || !token_tile || !weight_tile) return SIDA_EINVAL;

@@ -75,6 +75,13 @@ struct CopyTable {
 };
 int launch_expert_copy(const CopyTable &tbl, size_t expert_bytes, hipStream_t st);
 
+// The hash function (hash_fn.hip).  C is 64 or 128; ws holds 8*C floats per token.
+struct HashShape {
+    int32_t d_model, C, L, E, top_k;
+};
+int launch_hash_forward(const HashShape &sh, const float *params, const void *x, int32_t n_seq, int32_t seq_len,
+                        int32_t *ids, float *alpha, float *ws, hipStream_t st);
+
 constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)
 

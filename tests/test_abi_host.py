@@ -168,3 +168,12 @@ def test_tile_order_visits_every_tile_once():
     assert mixed != plain and sorted(mixed) == plain
     with pytest.raises(sm.SidaError):
         sm.tile_order(4, 5, 3)
+
+
+def test_hash_function_sizes():
+    cfg = sm.SidaHashConfig(768, 128, 6, 128, 3, 512)
+    C, d, L, E = 128, 768, 6, 128
+    assert sm.hash_param_count(cfg) == C * d + C + 2 * (8 * C * C + 8 * C) + L * E * C + L * E
+    assert sm.hash_param_count(cfg) == sum(int(np.prod(s)) for _, s in __import__("oracle.hash_fn").hash_fn.param_shapes(d, C, L, E))
+    assert sm.hash_workspace_bytes(cfg, 100) >= 4 * 8 * C * 100
+    assert sm.hash_param_count(sm.SidaHashConfig(768, 100, 6, 128, 3, 512)) == 0
