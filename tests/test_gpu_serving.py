@@ -95,3 +95,64 @@ def test_two_threads_sentence_sized_batches():
             y = bf16_tensor_to_f32(dev[b][3][l])[rows]
             assert_close(y, oracle_layer(wl, r, l, xs[b][l], tables[b][l], gates[b][l], rows), f"batch {b} layer {l}")
     r.close()
+
+
+def test_hash_thread_feeds_inference_thread():
+    """Algorithm 1 with both of its threads: the hash-building thread runs the hash function on the
+    GPU (its own stream), copies the predicted ids to the host and queues them; the inference
+    thread pops, plans and runs the MoE layers with the predicted ids and scaling factors."""
+    import paper_2310_18859_amd as sm
+    from oracle import hash_fn
+    from test_gpu_hash import make_params
+    from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+
+    d, C, L, E, T, n = 128, 64, 2, 10, 40, 5
+    wl = WORKLOADS[0].scaled(L=L, E=E, d_model=d, d_ff=256, T=T, S=8, W=4, name="serve-hash")
+    rng = np.random.default_rng(11)
+    cfg = sm.SidaHashConfig(d, C, L, E, 1, T)
+    params = make_params(rng, d, C, L, E)
+    r = make_runner(wl)
+    r.ctx.set_policy("belady", 2)
+    dev = r.dev
+    flat = np.concatenate([params[nm].reshape(-1) for nm, _ in hash_fn.param_shapes(d, C, L, E)])
+    pd = torch.from_numpy(flat).to(dev)
+    x_bits = [f32_to_bf16_bits(rng.standard_normal((T, d)).astype(np.float32)) for _ in range(n)]
+    xd = [torch.from_numpy(b).to(dev) for b in x_bits]
+    ids_d = [torch.zeros((L, T, 1), dtype=torch.int32, device=dev) for _ in range(n)]
+    alpha_d = [torch.zeros((L, T, 1), dtype=torch.float32, device=dev) for _ in range(n)]
+    ys = [[torch.zeros((T, d), dtype=torch.bfloat16, device=dev) for _ in range(L)] for _ in range(n)]
+    ws = torch.zeros(sm.hash_workspace_bytes(cfg, T), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    hash_stream = torch.cuda.Stream(device=dev)
+    tables = [None] * n
+
+    def hash_thread():
+        for b in range(n):
+            sm.hash_forward(cfg, pd, xd[b], 1, T, ids_d[b], alpha_d[b], ws, hash_stream)
+            hash_stream.synchronize()                     # the table must be complete before it is queued
+            tables[b] = ids_d[b].cpu().numpy().reshape(L, T)
+            r.push_table(b, tables[b])
+        r.ctx.queue_close()
+
+    th = threading.Thread(target=hash_thread)
+    th.start()
+    served = 0
+    while True:
+        try:
+            got = r.serve_next(lambda t: ([xd[t].view(torch.bfloat16)] * L, [ids_d[t][l].reshape(-1) for l in range(L)],
+                                          [alpha_d[t][l].reshape(-1) for l in range(L)], ys[t]), 5000)
+        except sm.SidaError as e:
+            assert e.code == -7
+            break
+        assert got is not None and got[0] == served
+        served += 1
+    th.join()
+    r.sync()
+    assert served == n
+    hw = r.host_weights.numpy()
+    for b in range(n):
+        alpha = alpha_d[b].cpu().numpy().reshape(L, T)
+        for l in range(L):
+            ref = oracle.moe_forward(x_bits[b], tables[b][l], alpha[l], [hw[l * E + e] for e in range(E)], d, 256)
+            assert_close(bf16_tensor_to_f32(ys[b][l]), ref, f"batch {b} layer {l}")
+    r.close()
