@@ -40,7 +40,7 @@ int make_events(sida_ctx *c)
 }
 
 // Upper bound of token tiles of a layer: every expert may end in a partial tile.
-size_t max_tiles(const sida_config &cfg, int32_t T) { return (size_t)T / kGemmTileM + (size_t)cfg.E + 1; }
+size_t max_tiles(const sida_config &cfg, int32_t T) { return (size_t)T / kGemmTileSmall + (size_t)cfg.E + 1; }
 
 void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
 {
@@ -155,10 +155,27 @@ struct LayerSchedule {
     LayerTable tbl;
     int32_t tile_begin[SIDA_MAX_E];
     int32_t m_tiles[SIDA_MAX_E];
-    int32_t m_tall[SIDA_MAX_E];       // leading tiles of the wave that belong to experts with > kGemmTileM tokens
+    int32_t m_tall[SIDA_MAX_E];       // leading tiles of the wave that belong to experts with more than one tile
 };
 
-void build_schedule(const sida_plan *p, LayerSchedule *s)
+// Token rows per tile for a layer.  A grouped GEMM is bound by the rows its tiles pull through LDS:
+// a tile of tile_m token rows and 256 weight rows costs tile_m + 256 rows per K-step whether or not
+// all its token rows exist.  64-row tiles pay when most experts have at most 64 tokens, i.e. when
+// halving the tile height adds few tiles: tiles(64) * 320 <= tiles(128) * 384.  (Measured on the
+// Switch-base-128 shape: 64-row tiles are 8-10 % faster at 8-16 tokens per expert, even at 64, and
+// 6 % slower at 128 tokens per expert.)
+int32_t choose_tile_m(const sida_plan *p)
+{
+    int64_t t64 = 0, t128 = 0;
+    for (int32_t i = 0; i < p->n_active; ++i) {
+        const int32_t n = p->counts[p->order[i]];
+        t64 += (n + kGemmTileSmall - 1) / kGemmTileSmall;
+        t128 += (n + kGemmTileM - 1) / kGemmTileM;
+    }
+    return 5 * t64 <= 6 * t128 ? kGemmTileSmall : kGemmTileM;
+}
+
+void build_schedule(const sida_plan *p, int32_t tile_m, LayerSchedule *s)
 {
     int32_t idx[SIDA_MAX_E];
     for (int32_t i = 0; i < p->n_active; ++i) idx[i] = p->order[i];     // already grouped by wave
@@ -167,6 +184,7 @@ void build_schedule(const sida_plan *p, LayerSchedule *s)
         return p->counts[a] > p->counts[b];
     });
     s->tbl.n = p->n_active;
+    s->tbl.tile_m = tile_m;
     for (int32_t w = 0; w < p->n_waves; ++w) s->tile_begin[w] = s->m_tiles[w] = s->m_tall[w] = 0;
     int32_t at = 0, cur = -1;
     for (int32_t i = 0; i < p->n_active; ++i) {
@@ -178,7 +196,7 @@ void build_schedule(const sida_plan *p, LayerSchedule *s)
             s->tile_begin[w] = at;
             cur = w;
         }
-        const int32_t n_t = (p->counts[e] + kGemmTileM - 1) / kGemmTileM;
+        const int32_t n_t = (p->counts[e] + tile_m - 1) / tile_m;
         s->m_tiles[w] += n_t;
         if (n_t > 1) s->m_tall[w] += n_t;                            // sorted by count: these come first
         at += n_t;
@@ -271,13 +289,13 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
         TimedKernel tk(c, SIDA_K_GEMM1);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(x ? x : ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
-                                                x ? ws.perm : nullptr, c->top_k));
+                                                x ? ws.perm : nullptr, c->top_k, s.tbl.tile_m));
     }
     {
         TimedKernel tk(c, SIDA_K_GEMM2);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, y ? y : ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
-                                                y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr));
+                                                y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr, s.tbl.tile_m));
     }
     return SIDA_OK;
 }
@@ -344,7 +362,7 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
         if (p->n_waves == 0) continue;
         const Ws ws = carve(c->cfg, p->T, ws_dev);
         LayerSchedule sched;
-        build_schedule(p, &sched);
+        build_schedule(p, choose_tile_m(p), &sched);
         const bool fused = c->fused;
         rc = launch_dispatch(c, a.x, a.ids, p->T, ws, &sched.tbl, compute,      // also expands sched.tbl into tiles
                              fused ? a.alpha : nullptr);
@@ -779,7 +797,7 @@ int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *wor
     rc = check_ws(c, plan->T, workspace_dev, workspace_bytes);
     if (rc) return rc;
     LayerSchedule sched;
-    build_schedule(plan, &sched);
+    build_schedule(plan, choose_tile_m(plan), &sched);
     const Ws ws = carve(c->cfg, plan->T, workspace_dev);
     rc = launch_tiles(c, sched, ws, static_cast<hipStream_t>(stream));
     if (rc) return rc;

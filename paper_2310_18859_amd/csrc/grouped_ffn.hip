@@ -105,7 +105,7 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     constexpr int LOADS = (BM + BN) / (RPL * NW);             // direct loads per thread per K-step
     constexpr int kSideBytes = FUSE == kPlain ? 0 : 512;      // per wavefront: row maps of a tile
     constexpr int kExtra = FUSE == kPlain ? 0 : 2;            // direct loads per thread per tile for them
-    static_assert(FUSE == kPlain || (BM == 128 && WM == 2), "row maps are laid out for 128-row tiles, two wavefront rows");
+    static_assert(FUSE == kPlain || ((BM == 128 || BM == 64) && WM == 2), "row maps are laid out for tiles of up to 128 rows, two wavefront rows");
     static_assert(BK == 64 || BK == 32, "K step");
     constexpr int MI = BM / (32 * WM);                        // 32-row MFMA blocks per wavefront along tokens
     constexpr int NI = BN / (32 * WN);                        //   ... along weight rows
@@ -227,9 +227,9 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     constexpr int RPI = 64 / LPR;                             // rows per store instruction
     static_assert(STORES == MI * (32 / RPI), "store count");
     static_assert(NW * 32 * kOutPitch <= kStageBytes, "staging fits in a stage");
-    // kScatter: this wavefront's 64 rows of the tile: perm -> side[0..63], gate_perm -> side[64..127]
+    // kScatter: this wavefront's BM/WM rows of the tile: perm -> side[0..63], gate_perm -> side[64..127]
     auto fetch_rows_out = [&](const Coord &c) {
-        const int r = c.row0 + min(wm * 64 + lane, c.rows - 1);
+        const int r = c.row0 + min(wm * (BM / WM) + lane, c.rows - 1);
         load_word_to_lds(perm + r, side);
         load_word_to_lds(gate_perm + r, side + 256);
     };
@@ -411,12 +411,30 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
 // Tile width of a launch: the shape whose busiest compute unit moves the fewest tile bytes through
 // its LDS, rounds of tiles times rows per K-step; a tie goes to the wide tile, which re-reads the
 // token rows half as often.
-bool wide_tiles_pay(int32_t m_tiles, int32_t N, hipStream_t st)
+bool wide_tiles_pay(int32_t m_tiles, int32_t N, int32_t tile_m, hipStream_t st)
 {
     const int64_t cus = persistent_grid(st);
-    const int64_t narrow = ((int64_t)m_tiles * (N / 128) + cus - 1) / cus * (128 + 128);
-    const int64_t wide = ((int64_t)m_tiles * (N / 256) + cus - 1) / cus * (128 + 256);
+    const int64_t narrow = ((int64_t)m_tiles * (N / 128) + cus - 1) / cus * (tile_m + 128);
+    const int64_t wide = ((int64_t)m_tiles * (N / 256) + cus - 1) / cus * (tile_m + 256);
     return wide <= narrow;
+}
+
+// One GEMM of the pair: BM = token rows per tile (64 or 128), wide or narrow tiles by the launch's
+// size, ring depth by the length of the K loop (a tile's K loop needs at least STAGES-1 steps of 64).
+template <int BM, bool RELU>
+int launch_shape(const void *A, void *C, const char *pool, size_t expert_bytes, size_t w_off, const TileDesc *tiles,
+                 int32_t m_tiles, int32_t m_tall, int N, int K, void *sink, const int32_t *perm, const float *gate_perm,
+                 int top_k, hipStream_t st, const LaunchEvents *ev)
+{
+    // N and K are multiples of 256 for every Switch shape; other widths fall back to 128-wide tiles
+    if (N % 256 == 0 && K >= 128 && wide_tiles_pay(m_tiles, N, BM, st))
+        return launch<BM, 256, 64, 2, 4, 3, RELU>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N, K, sink, perm,
+                                                  gate_perm, top_k, st, ev);
+    if (K < 192)
+        return launch<BM, 128, 64, 2, 4, 3, RELU>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N, K, sink, perm,
+                                                  gate_perm, top_k, st, ev);
+    return launch<BM, 128, 64, 2, 4, 4, RELU>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N, K, sink, perm,
+                                              gate_perm, top_k, st, ev);
 }
 
 }  // namespace
@@ -429,29 +447,26 @@ void forget_stream(hipStream_t st)
 
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev, const int32_t *perm, int32_t top_k)
+                     const LaunchEvents *ev, const int32_t *perm, int32_t top_k, int32_t tile_m)
 {
-    const float *gate_perm = nullptr;
-    // F and d are multiples of 256 for every Switch shape; other widths fall back to 128-wide tiles.
-    // A tile's K loop needs at least STAGES-1 steps of 64.
-    if (F % 256 == 0 && d >= 128 && wide_tiles_pay(m_tiles, F, st))
-        return launch<128, 256, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
-    if (d < 192)
-        return launch<128, 128, 64, 2, 4, 3, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
-    return launch<128, 128, 64, 2, 4, 4, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, gate_perm, top_k, st, ev);
+    if (tile_m == kGemmTileSmall)
+        return launch_shape<kGemmTileSmall, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm,
+                                                  nullptr, top_k, st, ev);
+    return launch_shape<kGemmTileM, true>(x_perm, h, pool, expert_bytes, 0, tiles, m_tiles, m_tall, F, d, sink, perm, nullptr,
+                                          top_k, st, ev);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev, const int32_t *perm, const float *gate_perm)
+                     const LaunchEvents *ev, const int32_t *perm, const float *gate_perm, int32_t tile_m)
 {
-    const int top_k = 1;                                     // scattering is only defined for one expert per token
     const size_t w_out = (size_t)F * (size_t)d * 2;          // W_out follows W_in in an expert's block
-    if (d % 256 == 0 && wide_tiles_pay(m_tiles, d, st))
-        return launch<128, 256, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
-    if (F < 192)
-        return launch<128, 128, 64, 2, 4, 3, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
-    return launch<128, 128, 64, 2, 4, 4, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm, gate_perm, top_k, st, ev);
+    // scattering is only defined for one expert per token: top_k = 1
+    if (tile_m == kGemmTileSmall)
+        return launch_shape<kGemmTileSmall, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm,
+                                                   gate_perm, 1, st, ev);
+    return launch_shape<kGemmTileM, false>(h, y_perm, pool, expert_bytes, w_out, tiles, m_tiles, m_tall, d, F, sink, perm,
+                                           gate_perm, 1, st, ev);
 }
 
 // ---- token-tile descriptors ----------------------------------------------------------------
@@ -469,7 +484,7 @@ __global__ __launch_bounds__(256) void build_tiles(const LayerTable tbl, const i
         slot = tbl.slot[tid];
         off = offsets[e];
         cnt = offsets[e + 1] - off;
-        n_t = (cnt + kGemmTileM - 1) / kGemmTileM;
+        n_t = (cnt + tbl.tile_m - 1) / tbl.tile_m;
     }
     int incl = n_t;
 #pragma unroll
@@ -484,8 +499,8 @@ __global__ __launch_bounds__(256) void build_tiles(const LayerTable tbl, const i
     for (int k = 0; k < n_t && at < max_tiles; ++k, ++at) {
         TileDesc t;
         t.slot = slot;
-        t.row0 = off + k * kGemmTileM;
-        t.rows = min(kGemmTileM, cnt - k * kGemmTileM);
+        t.row0 = off + k * tbl.tile_m;
+        t.rows = min(tbl.tile_m, cnt - k * tbl.tile_m);
         t.expert = e;
         tiles[at] = t;
     }

@@ -11,15 +11,16 @@ namespace sida {
 // tail of a launch).  Passed by value to the kernel that expands it into token-tile descriptors.
 struct LayerTable {
     int32_t n;                 // activated experts
+    int32_t tile_m;            // token rows per tile of this layer's grouped GEMMs: 64 or 128
     int16_t slot[256];         // pool slot of entry i
     uint8_t expert[256];       // expert id of entry i
 };
 
-// One token tile of the grouped GEMMs: up to kGemmTileM consecutive rows of one expert.
+// One token tile of the grouped GEMMs: up to tile_m (64 or 128) consecutive rows of one expert.
 struct TileDesc {
     int32_t slot;              // pool slot holding the expert's weights
     int32_t row0;              // first row in x_perm / h / y_perm
-    int32_t rows;              // 1..kGemmTileM
+    int32_t rows;              // 1..tile_m
     int32_t expert;
 };
 
@@ -42,7 +43,8 @@ int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void
                   const LaunchEvents *ev = nullptr, int32_t k = 1);
 // K-b: h = relu(x_perm W_in^T) then y_perm = h W_out^T for the experts in tbl.
 // tiles[0 .. m_tiles) are the token tiles of the experts to compute (see launch_build_tiles); the
-// first m_tall of them belong to experts with more than kGemmTileM tokens.
+// first m_tall of them belong to experts with more than one tile; tile_m = rows per tile (64 when
+// most experts of the layer have at most 64 tokens, 128 otherwise).
 // sink: kGemmSinkBytes of device scratch that absorbs the stores of rows past a tile's end.
 // With a row map (perm, and for GEMM 2 gate_perm) the gather / combine passes are folded in:
 // GEMM 1 then reads row r from x[perm[r] / k] (x_perm = x in token order, k rows per token), GEMM 2 writes
@@ -50,14 +52,14 @@ int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
-                     int32_t k = 1);
+                     int32_t k = 1, int32_t tile_m = 128);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
-                     const float *gate_perm = nullptr);
+                     const float *gate_perm = nullptr, int32_t tile_m = 128);
 // A stream is about to be destroyed: drop what is cached about it (its handle may be reused).
 void forget_stream(hipStream_t st);
-// Expands tbl into token tiles: entry i gets ceil(count_i / kGemmTileM) consecutive descriptors,
+// Expands tbl into token tiles: entry i gets ceil(count_i / tbl.tile_m) consecutive descriptors,
 // entries in table order; counts come from `offsets` (device).  At most max_tiles are written.
 int launch_build_tiles(const LayerTable &tbl, const int32_t *offsets, TileDesc *tiles, int32_t max_tiles,
                        hipStream_t st);
@@ -83,6 +85,7 @@ int launch_hash_forward(const HashShape &sh, const float *params, const void *x,
                         int32_t *ids, float *alpha, float *ws, hipStream_t st);
 
 constexpr int kGemmSinkBytes = 64 * 1024;
-constexpr int kGemmTileM = 128;   // token rows per GEMM tile (WaveTable::m_tiles is counted in these)
+constexpr int kGemmTileM = 128;   // token rows per GEMM tile of large launches
+constexpr int kGemmTileSmall = 64; // ... of small launches
 
 }  // namespace sida

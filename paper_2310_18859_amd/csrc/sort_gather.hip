@@ -124,7 +124,7 @@ __global__ __launch_bounds__(1024) void sort_scan(int32_t *__restrict__ block_hi
             slot = tbl.slot[tid];
             off = s_off[ex];
             cnt = s_off[ex + 1] - off;
-            n_t = (cnt + kGemmTileM - 1) / kGemmTileM;
+            n_t = (cnt + tbl.tile_m - 1) / tbl.tile_m;
         }
         __syncthreads();                                        // s_wsum is reused
         int inc2 = n_t;
@@ -143,8 +143,8 @@ __global__ __launch_bounds__(1024) void sort_scan(int32_t *__restrict__ block_hi
             for (int k = 0; k < n_t && at < max_tiles; ++k, ++at) {
                 TileDesc td;
                 td.slot = slot;
-                td.row0 = off + k * kGemmTileM;
-                td.rows = min(kGemmTileM, cnt - k * kGemmTileM);
+                td.row0 = off + k * tbl.tile_m;
+                td.rows = min(tbl.tile_m, cnt - k * tbl.tile_m);
                 td.expert = ex;
                 tiles[at] = td;
             }
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *_
             slot = tbl.slot[tid];
             off = s_off[ex];
             cnt = s_off[ex + 1] - off;
-            n_t = (cnt + kGemmTileM - 1) / kGemmTileM;
+            n_t = (cnt + tbl.tile_m - 1) / tbl.tile_m;
         }
         int inc2 = n_t;
         if (tid < 256) {
@@ -280,8 +280,8 @@ __global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *_
             for (int k = 0; k < n_t && at < max_tiles; ++k, ++at) {
                 TileDesc td;
                 td.slot = slot;
-                td.row0 = off + k * kGemmTileM;
-                td.rows = min(kGemmTileM, cnt - k * kGemmTileM);
+                td.row0 = off + k * tbl.tile_m;
+                td.rows = min(tbl.tile_m, cnt - k * tbl.tile_m);
                 td.expert = ex;
                 tiles[at] = td;
             }
@@ -337,6 +337,7 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
     const int n_chunks = (T + kChunk - 1) / kChunk;
     LayerTable none;
     none.n = 0;
+    none.tile_m = kGemmTileM;
     if (T <= kSmallT) {
         hipLaunchKernelGGL(sort_small, dim3(1), dim3(kSmallChunks * 64), 0, st, ids, T, E, counts, offsets, perm, inv,
                            alpha, alpha ? gate_perm : nullptr, tbl ? *tbl : none, tiles, max_tiles);

@@ -64,6 +64,43 @@ def test_small_shapes(name, L, E, d, F, T, zipf, S, W):
     say(f"  max rel err {err:.3e}")
 
 
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("name,E,d,F,T,zipf,rows_per_tile", [
+    # most experts have at most 64 tokens, the largest several hundred: 64-row tiles, several per expert
+    ("short-tiles", 40, 256, 512, 1500, 1.0, 64),
+    ("short-tiles-wide", 48, 768, 3072, 1700, 1.1, 64),      # both GEMMs take 256-wide tiles
+    # about 190 tokens per expert: 128-row tiles
+    ("tall-tiles", 8, 256, 512, 1500, None, 128),
+])
+def test_both_tile_heights(name, E, d, F, T, zipf, rows_per_tile, fused):
+    """The grouped GEMMs cut an expert's rows into tiles of 64 or 128 rows depending on the token
+    counts of the layer; checks the descriptors the device built and the layer output for each."""
+    say(f"layer parity: {name} fused={fused}")
+    wl = Workload(140 + len(name), name, 1, E, d, F, T, zipf, E, E)
+    r = make_runner(wl)
+    r.ctx.set_fusion(fused)
+    x_bits, ids, alpha = layer_inputs(wl, 0)
+    x, i, a, y = r.to_device(x_bits, ids, alpha)
+    plan = r.ctx.moe_plan(0, ids)
+    r.ctx.moe_layer_forward(plan, x, i, a, y, r.workspace, r.compute, r.copy)
+    r.sync()
+    counts = np.bincount(ids, minlength=E)
+    offsets = np.concatenate([[0], np.cumsum(counts)])
+    n_tiles = int(((counts + rows_per_tile - 1) // rows_per_tile).sum())
+    tiles = r.region(T, "tiles", torch.int32, (n_tiles, 4)).cpu().numpy()      # slot, row0, rows, expert
+    assert tiles[:, 2].max() == rows_per_tile and tiles[:, 2].min() >= 1
+    covered = np.zeros(T, np.int32)
+    for slot, row0, rows, e in tiles:
+        assert offsets[e] <= row0 and row0 + rows <= offsets[e + 1] and (row0 - offsets[e]) % rows_per_tile == 0
+        assert slot == plan.slot[e]
+        covered[row0:row0 + rows] += 1
+    assert np.all(covered == 1)
+    ref = oracle_layer(wl, r, 0, x_bits, ids, alpha)
+    err = assert_close(bf16_tensor_to_f32(y), ref, name)
+    say(f"  max rel err {err:.3e}")
+    r.close()
+
+
 def test_varying_T_including_empty_layers():
     say("layer parity: T changes per call, some calls empty")
     wl = Workload(120, "varT", 3, 6, 128, 256, 300, 1.0, 4, 2)
