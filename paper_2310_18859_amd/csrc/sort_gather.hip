@@ -188,41 +188,45 @@ __global__ __launch_bounds__(64) void sort_rank(const int32_t *__restrict__ ids,
     }
 }
 
-// The whole sort in one workgroup for layer calls of at most kSmallT tokens (one or two sequences
-// per batch, the paper's serving regime): wavefront w owns chunk w, the per-chunk histograms and
-// bases live in LDS, and the three launches above shrink to one.  Same results.
-constexpr int kSmallChunks = 8;
-constexpr int kSmallT = kSmallChunks * kChunk;
+// The whole sort in one workgroup for layer calls of up to 4096 tokens (from one or two sequences
+// per batch, the paper's serving regime, upwards): wavefront w owns chunks w*CPW .. w*CPW+CPW-1,
+// the per-chunk histograms and bases live in LDS, and the three launches above shrink to one.
+// Same results.  NWV wavefronts x CPW chunks of 256 tokens.  Measured: 9 us up to 2048 tokens and
+// 10 us (14 us when the gate values move along) at 4096 against 17-19 us for the three launches; at
+// 8192 tokens (16 x 2 chunks) 15 us and 24 us, the latter slower than the three launches.
+constexpr int kOneT = 4096;      // most tokens the single-workgroup sort takes
 
-__global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *__restrict__ ids, int T, int E,
-                                                                int32_t *__restrict__ counts,
-                                                                int32_t *__restrict__ offsets,
-                                                                int32_t *__restrict__ perm, int32_t *__restrict__ inv,
-                                                                const float *__restrict__ alpha,
-                                                                float *__restrict__ gate_perm, const LayerTable tbl,
-                                                                TileDesc *__restrict__ tiles, int max_tiles)
+template <int NWV, int CPW>
+__global__ __launch_bounds__(NWV * 64) void sort_one(const int32_t *__restrict__ ids, int T, int E,
+                                                     int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+                                                     int32_t *__restrict__ perm, int32_t *__restrict__ inv,
+                                                     const float *__restrict__ alpha, float *__restrict__ gate_perm,
+                                                     const LayerTable tbl, TileDesc *__restrict__ tiles, int max_tiles)
 {
-    __shared__ int hist[kSmallChunks][kMaxE];      // per-chunk histogram, then first output row of (chunk, expert)
+    constexpr int NCH = NWV * CPW;
+    __shared__ int hist[NCH][kMaxE];               // per-chunk histogram, then first output row of (chunk, expert)
     __shared__ int s_off[kMaxE + 1];
     __shared__ int s_wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    for (int i = tid; i < kSmallChunks * kMaxE; i += kSmallChunks * 64) (&hist[0][0])[i] = 0;
+    for (int i = tid; i < NCH * kMaxE; i += NWV * 64) (&hist[0][0])[i] = 0;
     __syncthreads();
 
-    int my_id[kChunk / 64];
+    int my_id[CPW][kChunk / 64];
 #pragma unroll
-    for (int r = 0; r < kChunk / 64; ++r) {
-        const int t = wv * kChunk + r * 64 + lane;
-        my_id[r] = t < T ? clamp_id(ids[t], E) : -1;
-        if (my_id[r] >= 0) atomicAdd(&hist[wv][my_id[r]], 1);
-    }
+    for (int j = 0; j < CPW; ++j)
+#pragma unroll
+        for (int r = 0; r < kChunk / 64; ++r) {
+            const int t = (wv * CPW + j) * kChunk + r * 64 + lane;
+            my_id[j][r] = t < T ? clamp_id(ids[t], E) : -1;
+            if (my_id[j][r] >= 0) atomicAdd(&hist[wv * CPW + j][my_id[j][r]], 1);
+        }
     __syncthreads();
 
     // expert totals -> offsets (threads 0..255: one expert each), then the bases of every chunk
     int total = 0, incl = 0;
     if (tid < 256) {
         if (tid < E)
-            for (int c = 0; c < kSmallChunks; ++c) total += hist[c][tid];
+            for (int c = 0; c < NCH; ++c) total += hist[c][tid];
         incl = total;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -244,7 +248,7 @@ __global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *_
                 s_off[E] = T;
             }
             int run = excl;
-            for (int c = 0; c < kSmallChunks; ++c) {
+            for (int c = 0; c < NCH; ++c) {
                 const int v = hist[c][tid];
                 hist[c][tid] = run;
                 run += v;
@@ -288,29 +292,33 @@ __global__ __launch_bounds__(kSmallChunks * 64) void sort_small(const int32_t *_
         }
     }
 
-    // ranks: wavefront w walks its chunk in rounds of 64 tokens (LDS accesses of one wavefront
+    // ranks: wavefront w walks its chunks in rounds of 64 tokens (LDS accesses of one wavefront
     // execute in program order, so the reads of a round precede its updates)
     const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int r = 0; r < kChunk / 64; ++r) {
-        const int t = wv * kChunk + r * 64 + lane;
-        const bool live = my_id[r] >= 0;
-        const int k = live ? my_id[r] : 0;
-        unsigned long long same = __ballot(live);
+    for (int j = 0; j < CPW; ++j) {
+        int *next_row = hist[wv * CPW + j];
 #pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            const unsigned long long b = __ballot((k >> bit) & 1);
-            same &= ((k >> bit) & 1) ? b : ~b;
-        }
-        int row = 0;
-        if (live) row = hist[wv][k] + __popcll(same & below);
-        __builtin_amdgcn_wave_barrier();
-        if (live && (same & below) == 0) hist[wv][k] += __popcll(same);
-        __builtin_amdgcn_wave_barrier();
-        if (live) {
-            perm[row] = t;
-            inv[t] = row;
-            if (alpha) gate_perm[row] = alpha[t];
+        for (int r = 0; r < kChunk / 64; ++r) {
+            const int t = (wv * CPW + j) * kChunk + r * 64 + lane;
+            const bool live = my_id[j][r] >= 0;
+            const int k = live ? my_id[j][r] : 0;
+            unsigned long long same = __ballot(live);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const unsigned long long b = __ballot((k >> bit) & 1);
+                same &= ((k >> bit) & 1) ? b : ~b;
+            }
+            int row = 0;
+            if (live) row = next_row[k] + __popcll(same & below);
+            __builtin_amdgcn_wave_barrier();
+            if (live && (same & below) == 0) next_row[k] += __popcll(same);
+            __builtin_amdgcn_wave_barrier();
+            if (live) {
+                perm[row] = t;
+                inv[t] = row;
+                if (alpha) gate_perm[row] = alpha[t];
+            }
         }
     }
 }
@@ -338,9 +346,15 @@ int launch_sort(const int32_t *ids, int32_t T, int32_t E, int32_t *counts, int32
     LayerTable none;
     none.n = 0;
     none.tile_m = kGemmTileM;
-    if (T <= kSmallT) {
-        hipLaunchKernelGGL(sort_small, dim3(1), dim3(kSmallChunks * 64), 0, st, ids, T, E, counts, offsets, perm, inv,
-                           alpha, alpha ? gate_perm : nullptr, tbl ? *tbl : none, tiles, max_tiles);
+    if (T <= kOneT) {
+        const LayerTable &t = tbl ? *tbl : none;
+        float *gp = alpha ? gate_perm : nullptr;
+        if (T <= 8 * kChunk)
+            hipLaunchKernelGGL((sort_one<8, 1>), dim3(1), dim3(512), 0, st, ids, T, E, counts, offsets, perm, inv, alpha, gp, t,
+                               tiles, max_tiles);
+        else
+            hipLaunchKernelGGL((sort_one<16, 1>), dim3(1), dim3(1024), 0, st, ids, T, E, counts, offsets, perm, inv, alpha, gp,
+                               t, tiles, max_tiles);
         return (int)hipGetLastError();
     }
     hipLaunchKernelGGL(sort_hist, dim3(n_chunks), dim3(64), 0, st, ids, T, E, block_hist);

@@ -26,7 +26,9 @@ def ids_for(rng, kind, T, E):
     (1, 1, "one"), (1, 8, "uniform"), (63, 8, "uniform"), (64, 8, "zipf"), (65, 3, "uniform"),
     (255, 64, "zipf"), (256, 256, "uniform"), (257, 256, "zipf"), (1000, 7, "one"), (1023, 128, "zipf"),
     (2047, 200, "zipf"), (2048, 128, "uniform"), (2049, 128, "zipf"),    # around the single-workgroup sort's limit
-    (5000, 256, "uniform"), (4097, 64, "zipf"), (16384, 128, "zipf"), (32768, 256, "zipf"),
+    (4095, 128, "zipf"), (4096, 256, "uniform"), (5000, 256, "uniform"), (4097, 64, "zipf"),
+    (8191, 128, "zipf"), (8192, 256, "zipf"), (8193, 128, "uniform"),                    # ... and its larger shapes
+    (16384, 128, "zipf"), (32768, 256, "zipf"),
     (65536, 128, "uniform"), (65537, 256, "zipf"), (70001, 64, "zipf"),
 ])
 def test_dispatch_bit_exact(T, E, kind):
