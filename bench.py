@@ -31,14 +31,14 @@ H2D_PEAK_GBS = 64.0            # PCIe Gen5 x16, one direction
 # Source: profiles/grouped_ffn_switch-base-128.hbm_traffic.txt
 # key: (workload name, mode, kernel) -> bytes per launch (fetch + write).
 MEASURED_TRAFFIC = {
-    ("switch-base-128-T16384", "resident", "gemm1"): (384096.3 * 2.0 + 98886.0) * 1024,
-    ("switch-base-128-T16384", "resident", "gemm2"): (406913.1 * 2.0 + 24806.8) * 1024,
-    ("switch-base-128-T16384", "resident_fused", "gemm1"): (383938.7 * 2.0 + 98879.2) * 1024,
-    ("switch-base-128-T16384", "resident_fused", "gemm2"): (406925.8 * 2.0 + 24803.2) * 1024,
-    ("switch-base-128-T16384", "streaming", "gemm1"): (54154.6 * 2.0 + 12368.4) * 1024,
+    ("switch-base-128-T16384", "resident", "gemm1"): (383981.4 * 2.0 + 98882.5) * 1024,
+    ("switch-base-128-T16384", "resident", "gemm2"): (406925.4 * 2.0 + 24806.7) * 1024,
+    ("switch-base-128-T16384", "resident_fused", "gemm1"): (383880.2 * 2.0 + 98878.8) * 1024,
+    ("switch-base-128-T16384", "resident_fused", "gemm2"): (406984.6 * 2.0 + 24810.5) * 1024,
+    ("switch-base-128-T16384", "streaming", "gemm1"): (54668.1 * 2.0 + 12371.1) * 1024,
     # 126 launches with 128 x 128 tiles and 18 with 128 x 256 tiles per 2+1 steps: weighted mean
-    ("switch-base-128-T16384", "streaming", "gemm2"): ((62001.2 * 126 + 95657.5 * 18) / 144 * 2.0
-                                                       + (1928.7 * 126 + 11584.5 * 18) / 144) * 1024,
+    ("switch-base-128-T16384", "streaming", "gemm2"): ((62001.6 * 126 + 95655.1 * 18) / 144 * 2.0
+                                                       + (1928.6 * 126 + 11584.5 * 18) / 144) * 1024,
 }
 
 

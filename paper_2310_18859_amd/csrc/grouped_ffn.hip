@@ -133,13 +133,13 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
     const int sub_row = lane / PPR;
     const int piece = (lane % PPR) ^ (BK == 64 ? sub_row : (sub_row >> 2) & 3);   // logical piece this lane fetches
     struct Coord {
-        int row0, rows, nt, k0;
+        int row0, rows, nt;
     };
     auto locate = [&](int i, Coord *c) {                      // i-th tile of this workgroup; returns its pool slot
         int mt, nt;
         map_tile((int)blockIdx.x + i * G, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
         const TileDesc td = tiles[mt];                        // uniform address: a scalar load
-        *c = Coord{td.row0, td.rows, nt, (mt + nt) % nk};
+        *c = Coord{td.row0, td.rows, nt};
         return td.slot;
     };
     char *side = lds + kRingBytes + wv * kSideBytes;          // this wavefront's row maps (FUSE != kPlain)
@@ -149,13 +149,6 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
         for (int i = 0; i < 2; ++i)
             load_word_to_lds(perm + c.row0 + min(i * 64 + lane, c.rows - 1), side + i * 256);
     };
-    // A tile walks its K-steps in rotated order, starting at step k0 = (token tile + weight-row tile)
-    // mod nk and wrapping at the end of the rows (the sum does not depend on the order).  Tiles that
-    // run at the same time on an XCD and share an operand (the weight-row tiles of one token tile,
-    // the token tiles of a many-token expert) then ask for a given 128-byte piece at different
-    // times: the first one takes the L2 miss, the others find the piece in the L2 instead of all
-    // waiting for the same fill with the latency of a miss.
-    int k_at = 0;                                             // K-step the next issue() fetches
     auto point = [&](const Coord &c, int slot, const char *(&p)[LOADS]) {
         const char *Wt = pool + (size_t)slot * expert_bytes + w_off + (size_t)c.nt * BN * K * 2;
 #pragma unroll
@@ -167,20 +160,17 @@ __global__ __launch_bounds__(WM * WN * 64) void grouped_gemm_nt(const __bf16 *__
                 src = reinterpret_cast<const int *>(side)[ra];
                 if (top_k != 1) src /= top_k;
             }
-            p[j] = (r < BM ? reinterpret_cast<const char *>(A) + (size_t)src * K * 2
-                           : Wt + (size_t)(r - BM) * K * 2) + piece * 16 + c.k0 * kRowBytes;
+            p[j] = r < BM ? reinterpret_cast<const char *>(A) + (size_t)src * K * 2 + piece * 16
+                          : Wt + (size_t)(r - BM) * K * 2 + piece * 16;
         }
-        k_at = c.k0;
     };
     int wr_off = 0;                                           // ring offset of the stage filled next
     auto issue = [&](const char *(&p)[LOADS]) {               // next K-step of the tile p points into
         char *dst = lds + wr_off + wv * LOADS * 1024;
-        const bool wrap = ++k_at == nk;                       // uniform
-        if (wrap) k_at = 0;
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             load_to_lds(p[j], dst + j * 1024);
-            p[j] += wrap ? kRowBytes - K * 2 : kRowBytes;
+            p[j] += kRowBytes;
         }
         wr_off = wr_off + kStageBytes == kRingBytes ? 0 : wr_off + kStageBytes;
     };
