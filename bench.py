@@ -168,6 +168,35 @@ def serve_leg(wl, hw, S, W, policy, look, n_batches, warm, T_b):
             "activated_per_batch": active / timed, "h2d_GBps": misses * wl.expert_bytes / dt / 1e9}
 
 
+def hash_leg(wl, C=128, seq_len=128):
+    """Times sida_hash_forward (Section 3.2.2) with random parameters on 1, 8 and 64 sequences."""
+    import numpy as np
+    import torch
+    from paper_2310_18859_amd.binding import SidaHashConfig, hash_forward, hash_param_count, hash_workspace_bytes
+    from workloads import f32_to_bf16_bits
+
+    cfg = SidaHashConfig(wl.d_model, C, wl.L, wl.E, 1, seq_len)
+    rng = np.random.default_rng(20231018)
+    params = torch.from_numpy((0.1 * rng.standard_normal(hash_param_count(cfg))).astype(np.float32)).cuda()
+    st = torch.cuda.Stream()
+    rows = []
+    for n_seq in (1, 8, 64):
+        n = n_seq * seq_len
+        x = torch.from_numpy(f32_to_bf16_bits(rng.standard_normal((n, wl.d_model)).astype(np.float32))).cuda()
+        ids = torch.empty((wl.L, n, 1), dtype=torch.int32, device="cuda")
+        alpha = torch.empty((wl.L, n, 1), dtype=torch.float32, device="cuda")
+        ws = torch.empty(hash_workspace_bytes(cfg, n), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for timed in (False, True):
+            t0 = time.perf_counter()
+            for _ in range(20):
+                hash_forward(cfg, params, x, n_seq, seq_len, ids, alpha, ws, st)
+            st.synchronize()
+            dt = (time.perf_counter() - t0) / 20
+        rows.append({"sequences": n_seq, "seq_len": seq_len, "ms": 1e3 * dt, "tokens_per_s": n / dt})
+    return {"config": {"d_model": wl.d_model, "C": C, "L": wl.L, "E": wl.E, "top_k": 1}, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -343,6 +372,12 @@ def main():
         r3.close()
         log(f"[bench] large-M experts alone: gemm1 {kern3['gemm1']['avg_us']:.1f} us, gemm2 {kern3['gemm2']['avg_us']:.1f} us")
 
+    # ---- the hash function's forward pass (predicts the ids / alpha table of a batch) ---------
+    hash_fn = None
+    if a.only == "both" and not a.tokens:
+        hash_fn = hash_leg(wl)
+        log("[bench] hash function: " + ", ".join(f"{r['sequences']} x {r['seq_len']} tokens {r['ms']:.3f} ms" for r in hash_fn["rows"]))
+
     tokens_per_step = wl.L * wl.T
     main_mode = "streaming" if "streaming" in result else "resident"
     main_steps = a.steps if main_mode == "streaming" else a.resident_steps
@@ -398,6 +433,8 @@ def main():
         line[mode] = e
     if "top_k" in result:
         line["top_k"] = result["top_k"]
+    if hash_fn:
+        line["hash_fn"] = hash_fn
     if serving:
         line["serving"] = serving
     if large_m:
