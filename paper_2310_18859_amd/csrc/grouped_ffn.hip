@@ -410,13 +410,16 @@ int launch(const void *A, void *C, const char *pool, size_t expert_bytes, size_t
 
 // Tile width of a launch: the shape whose busiest compute unit moves the fewest tile bytes through
 // its LDS, rounds of tiles times rows per K-step; a tie goes to the wide tile, which re-reads the
-// token rows half as often.
-bool wide_tiles_pay(int32_t m_tiles, int32_t N, int32_t tile_m, hipStream_t st)
+// token rows half as often.  For GEMM 2 (K = d_ff, four times fewer and longer tiles) the wide tile
+// is charged 9/8 of its rows: measured on the resident Switch shapes, 128-wide tiles are 5 % and
+// 2 % faster there at 100 and 205 token tiles (model 768 : 768 and 1280 : 1152) and 10 % and 8 %
+// slower at 420 and 330 (2560 : 1920, 2816 : 2304).
+bool wide_tiles_pay(int32_t m_tiles, int32_t N, int32_t tile_m, bool gemm2, hipStream_t st)
 {
     const int64_t cus = persistent_grid(st);
     const int64_t narrow = ((int64_t)m_tiles * (N / 128) + cus - 1) / cus * (tile_m + 128);
     const int64_t wide = ((int64_t)m_tiles * (N / 256) + cus - 1) / cus * (tile_m + 256);
-    return wide <= narrow;
+    return (gemm2 ? wide * 9 : wide * 8) <= narrow * 8;
 }
 
 // One GEMM of the pair: BM = token rows per tile (64 or 128), wide or narrow tiles by the launch's
@@ -427,7 +430,7 @@ int launch_shape(const void *A, void *C, const char *pool, size_t expert_bytes, 
                  int top_k, hipStream_t st, const LaunchEvents *ev)
 {
     // N and K are multiples of 256 for every Switch shape; other widths fall back to 128-wide tiles
-    if (N % 256 == 0 && K >= 128 && wide_tiles_pay(m_tiles, N, BM, st))
+    if (N % 256 == 0 && K >= 128 && wide_tiles_pay(m_tiles, N, BM, !RELU, st))
         return launch<BM, 256, 64, 2, 4, 3, RELU>(A, C, pool, expert_bytes, w_off, tiles, m_tiles, m_tall, N, K, sink, perm,
                                                   gate_perm, top_k, st, ev);
     if (K < 192)
