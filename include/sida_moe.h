@@ -304,7 +304,8 @@ int sida_combine(sida_ctx *ctx, const float *alpha_dev, int32_t T, void *y_dev,
  * [L, n_seq * seq_len, top_k] - layer l's slice is exactly the ids / alpha array that
  * sida_moe_plan (after a copy to the host) and sida_moe_layer_forward take (with sida_set_top_k).
  * workspace_dev: device, 256-byte aligned, >= sida_hash_workspace_bytes(n_seq * seq_len).
- * Limits: C is 64 or 128; E <= SIDA_MAX_E; L*E <= 8192; top_k <= min(E, SIDA_MAX_TOP_K);
+ * Limits: C is 64 or 128; d_model a multiple of 8, 8 .. 8192; E <= SIDA_MAX_E; L*E <= 8192;
+ * top_k <= min(E, SIDA_MAX_TOP_K);
  * seq_len <= max_seq_len <= 4096.  Asynchronous on `stream`. */
 typedef struct sida_hash_config {
     int32_t d_model;      /* embedding width                       */

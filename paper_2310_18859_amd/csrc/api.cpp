@@ -823,7 +823,7 @@ int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, vo
 namespace {
 bool hash_cfg_ok(const sida_hash_config *h)
 {
-    return h && (h->C == 64 || h->C == 128) && h->d_model >= 8 && h->d_model <= 8192 && h->L >= 1 && h->E >= 1 &&
+    return h && (h->C == 64 || h->C == 128) && h->d_model >= 8 && h->d_model <= 8192 && h->d_model % 8 == 0 && h->L >= 1 && h->E >= 1 &&
            h->E <= SIDA_MAX_E && (int64_t)h->L * h->E <= 8192 && h->top_k >= 1 && h->top_k <= SIDA_MAX_TOP_K &&
            h->top_k <= h->E && h->max_seq_len >= 1 && h->max_seq_len <= 4096;
 }

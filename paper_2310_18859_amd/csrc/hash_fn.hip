@@ -8,7 +8,9 @@
 // the residual adds the token's own compressed embedding; alpha = SoftMax probability of the
 // expert within its layer's head; the k largest are kept, ties to the lower expert id.
 //
-// A lightweight network (a few MFLOP per token): plain fp32 kernels, one launch per stage.  The
+// A lightweight network (a few MFLOP per token): plain fp32 kernels, one launch per stage (the
+// dense stages are fp32 contractions; the fp32 matrix-core rate of this chip equals its vector
+// rate, and bf16 inputs would move the predicted probabilities by more than the parity bound).  The
 // recurrent part keeps a gate row of W_hh in the registers of each of the 4C threads of a
 // sequence's workgroup and the state in LDS; SparseMax finds its threshold by bisection on
 // sum(max(s - tau, 0)) = 1 and then takes the closed form on the support that bisection found.
@@ -39,36 +41,76 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// c0[n, j] = b_in[j] + sum_i x[n, i] * w_in[j, i].  One workgroup of C threads per token.
-template <int C>
+// The three dense stages (compress, gate pre-activations, heads) take kTokenBlock tokens per
+// workgroup: a thread owns one output unit, reads its weight row once and applies it to every
+// token of the block (the tokens' inputs sit in LDS and are read as broadcasts), so a weight matrix
+// is fetched once per block instead of once per token.  Each (token, unit) sum runs in index order.
+constexpr int kTokenBlock = 8;
+
+// c0[n, j] = b_in[j] + sum_i x[n, i] * w_in[j, i].  One workgroup of C threads per block of TB tokens.
+template <int C, int TB>
 __global__ __launch_bounds__(C) void hash_compress(const __bf16 *__restrict__ x, const float *__restrict__ w_in,
-                                                   const float *__restrict__ b_in, int d, float *__restrict__ c0)
+                                                   const float *__restrict__ b_in, int d, int n_tokens,
+                                                   float *__restrict__ c0)
 {
-    extern __shared__ float xs[];                              // the token's embedding, fp32
-    const int n = blockIdx.x, j = threadIdx.x;
-    for (int i = j; i < d; i += C) xs[i] = (float)x[(size_t)n * d + i];
+    extern __shared__ __attribute__((aligned(16))) float xs[];                              // [TB][d] the tokens' embeddings, fp32
+    const int n0 = blockIdx.x * TB, j = threadIdx.x;
+    const int nb = min(TB, n_tokens - n0);
+    for (int i = j; i < TB * d; i += C) {
+        const int tb = i / d;
+        xs[i] = tb < nb ? (float)x[(size_t)n0 * d + i] : 0.f;
+    }
     __syncthreads();
-    const float *w = w_in + (size_t)j * d;
-    float acc = b_in[j];
-    for (int i = 0; i < d; ++i) acc += xs[i] * w[i];
-    c0[(size_t)n * C + j] = acc;
+    const float4 *w = reinterpret_cast<const float4 *>(w_in + (size_t)j * d);
+    float acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = b_in[j];
+    for (int i = 0; i < d / 4; ++i) {
+        const float4 wv = w[i];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const float4 xv = *reinterpret_cast<const float4 *>(xs + tb * d + 4 * i);
+            acc[tb] += xv.x * wv.x;
+            acc[tb] += xv.y * wv.y;
+            acc[tb] += xv.z * wv.z;
+            acc[tb] += xv.w * wv.w;
+        }
+    }
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+        if (tb < nb) c0[(size_t)(n0 + tb) * C + j] = acc[tb];
 }
 
-// pre[n, g] = b_ih[g] + b_hh[g] + sum_i in[n, i] * w_ih[g, i].  One workgroup of 4C threads per token.
-template <int C>
+// pre[n, g] = b_ih[g] + b_hh[g] + sum_i in[n, i] * w_ih[g, i].  One workgroup of 4C threads per block of TB tokens.
+template <int C, int TB>
 __global__ __launch_bounds__(4 * C) void hash_gates_in(const float *__restrict__ in, const float *__restrict__ w_ih,
                                                        const float *__restrict__ b_ih, const float *__restrict__ b_hh,
-                                                       float *__restrict__ pre)
+                                                       int n_tokens, float *__restrict__ pre)
 {
-    __shared__ float row[C];
-    const int n = blockIdx.x, g = threadIdx.x;
-    if (g < C) row[g] = in[(size_t)n * C + g];
+    __shared__ __attribute__((aligned(16))) float row[TB][C];
+    const int n0 = blockIdx.x * TB, g = threadIdx.x;
+    const int nb = min(TB, n_tokens - n0);
+    for (int i = g; i < TB * C; i += 4 * C) (&row[0][0])[i] = i / C < nb ? in[(size_t)n0 * C + i] : 0.f;
     __syncthreads();
-    const float *w = w_ih + (size_t)g * C;
-    float acc = b_ih[g] + b_hh[g];
-#pragma unroll 8
-    for (int i = 0; i < C; ++i) acc += row[i] * w[i];
-    pre[(size_t)n * 4 * C + g] = acc;
+    const float4 *w = reinterpret_cast<const float4 *>(w_ih + (size_t)g * C);
+    float acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = b_ih[g] + b_hh[g];
+#pragma unroll 4
+    for (int i = 0; i < C / 4; ++i) {
+        const float4 wv = w[i];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const float4 xv = *reinterpret_cast<const float4 *>(&row[tb][4 * i]);
+            acc[tb] += xv.x * wv.x;
+            acc[tb] += xv.y * wv.y;
+            acc[tb] += xv.z * wv.z;
+            acc[tb] += xv.w * wv.w;
+        }
+    }
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+        if (tb < nb) pre[(size_t)(n0 + tb) * 4 * C + g] = acc[tb];
 }
 
 // The recurrence of one LSTM layer.  One workgroup of 4C threads per sequence: thread g owns gate
@@ -157,28 +199,45 @@ __global__ __launch_bounds__(64) void hash_attention(const float *__restrict__ h
     }
 }
 
-// Heads: per MoE layer l the E logits of the token, their SoftMax, and the k most probable experts.
-// One workgroup of 256 threads per token; wavefront w takes layers w, w+4, ...
-template <int C>
+// Heads: per MoE layer l the E logits of a token, their SoftMax, and the k most probable experts.
+// One workgroup of 256 threads per block of TB tokens; wavefront w takes the (token, layer) pairs
+// w, w+4, ...
+template <int C, int TB>
 __global__ __launch_bounds__(256) void hash_heads(const float *__restrict__ r, const float *__restrict__ w_out,
                                                   const float *__restrict__ b_out, int L, int E, int top_k,
                                                   int n_tokens, int32_t *__restrict__ ids, float *__restrict__ alpha)
 {
-    extern __shared__ float logit[];                           // [L*E]
-    __shared__ float row[C];
-    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < C) row[tid] = r[(size_t)n * C + tid];
+    extern __shared__ __attribute__((aligned(16))) float logit[];                           // [TB][L*E]
+    __shared__ __attribute__((aligned(16))) float row[TB][C];
+    const int n0 = blockIdx.x * TB, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int nb = min(TB, n_tokens - n0);
+    const int LE = L * E;
+    for (int i = tid; i < TB * C; i += 256) (&row[0][0])[i] = i / C < nb ? r[(size_t)n0 * C + i] : 0.f;
     __syncthreads();
-    for (int o = tid; o < L * E; o += 256) {
-        const float *w = w_out + (size_t)o * C;
-        float acc = b_out[o];
-#pragma unroll 8
-        for (int i = 0; i < C; ++i) acc += row[i] * w[i];
-        logit[o] = acc;
+    for (int o = tid; o < LE; o += 256) {
+        const float4 *w = reinterpret_cast<const float4 *>(w_out + (size_t)o * C);
+        float acc[TB];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[tb] = b_out[o];
+#pragma unroll 4
+        for (int i = 0; i < C / 4; ++i) {
+            const float4 wv4 = w[i];
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const float4 xv = *reinterpret_cast<const float4 *>(&row[tb][4 * i]);
+                acc[tb] += xv.x * wv4.x;
+                acc[tb] += xv.y * wv4.y;
+                acc[tb] += xv.z * wv4.z;
+                acc[tb] += xv.w * wv4.w;
+            }
+        }
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) logit[tb * LE + o] = acc[tb];
     }
     __syncthreads();
-    for (int l = wv; l < L; l += 4) {
-        float *z = logit + l * E;
+    for (int pair = wv; pair < nb * L; pair += 4) {
+        const int tb = pair / L, l = pair % L, n = n0 + tb;
+        float *z = logit + tb * LE + l * E;
         float mx = -FLT_MAX;
         for (int e = lane; e < E; e += 64) mx = fmaxf(mx, z[e]);
         mx = wave_max(mx);
@@ -227,14 +286,41 @@ int run(const HashShape &sh, const float *p, const void *x, int n_seq, int T, in
     // workspace
     float *c0 = ws, *pre = c0 + (size_t)N * C, *h1 = pre + (size_t)N * 4 * C, *h2 = h1 + (size_t)N * C,
           *r = h2 + (size_t)N * C;
-    hipLaunchKernelGGL(hash_compress<C>, dim3(N), dim3(C), d * sizeof(float), st, (const __bf16 *)x, w_in, b_in, d, c0);
-    hipLaunchKernelGGL(hash_gates_in<C>, dim3(N), dim3(4 * C), 0, st, c0, w_ih1, b_ih1, b_hh1, pre);
+    // Tokens per workgroup of the dense stages: 8 when that still gives every compute unit several
+    // workgroups, fewer for short batches (one 128-token sequence: 1, as many workgroups as tokens),
+    // and never more than fit 48 KiB of LDS.
+    constexpr size_t kLdsCap = 48 * 1024;
+    const int want = N >= 4096 ? kTokenBlock : N >= 1024 ? 2 : 1;
+    auto block_for = [&](size_t bytes_per_token) {
+        int tb = want;
+        while (tb > 1 && tb * bytes_per_token > kLdsCap) tb = tb == kTokenBlock ? 2 : 1;
+        return tb;
+    };
+    auto blocks = [&](int tb) { return dim3((N + tb - 1) / tb); };
+    const size_t x_bytes = d * sizeof(float), le_bytes = (size_t)sh.L * sh.E * sizeof(float);
+    const __bf16 *xb = (const __bf16 *)x;
+    switch (block_for(x_bytes)) {
+        case kTokenBlock: hipLaunchKernelGGL((hash_compress<C, kTokenBlock>), blocks(kTokenBlock), dim3(C), kTokenBlock * x_bytes, st, xb, w_in, b_in, d, N, c0); break;
+        case 2: hipLaunchKernelGGL((hash_compress<C, 2>), blocks(2), dim3(C), 2 * x_bytes, st, xb, w_in, b_in, d, N, c0); break;
+        default: hipLaunchKernelGGL((hash_compress<C, 1>), blocks(1), dim3(C), x_bytes, st, xb, w_in, b_in, d, N, c0); break;
+    }
+    auto gates = [&](const float *in, const float *w_ih, const float *b_ih, const float *b_hh) {
+        switch (want) {
+            case kTokenBlock: hipLaunchKernelGGL((hash_gates_in<C, kTokenBlock>), blocks(kTokenBlock), dim3(4 * C), 0, st, in, w_ih, b_ih, b_hh, N, pre); break;
+            case 2: hipLaunchKernelGGL((hash_gates_in<C, 2>), blocks(2), dim3(4 * C), 0, st, in, w_ih, b_ih, b_hh, N, pre); break;
+            default: hipLaunchKernelGGL((hash_gates_in<C, 1>), blocks(1), dim3(4 * C), 0, st, in, w_ih, b_ih, b_hh, N, pre); break;
+        }
+    };
+    gates(c0, w_ih1, b_ih1, b_hh1);
     hipLaunchKernelGGL(hash_lstm<C>, dim3(n_seq), dim3(4 * C), 0, st, pre, w_hh1, T, h1);
-    hipLaunchKernelGGL(hash_gates_in<C>, dim3(N), dim3(4 * C), 0, st, h1, w_ih2, b_ih2, b_hh2, pre);
+    gates(h1, w_ih2, b_ih2, b_hh2);
     hipLaunchKernelGGL(hash_lstm<C>, dim3(n_seq), dim3(4 * C), 0, st, pre, w_hh2, T, h2);
     hipLaunchKernelGGL(hash_attention<C>, dim3(N), dim3(64), T * sizeof(float), st, h2, c0, T, r);
-    hipLaunchKernelGGL(hash_heads<C>, dim3(N), dim3(256), (size_t)sh.L * sh.E * sizeof(float), st, r, w_out, b_out, sh.L,
-                       sh.E, sh.top_k, N, ids, alpha);
+    switch (block_for(le_bytes)) {
+        case kTokenBlock: hipLaunchKernelGGL((hash_heads<C, kTokenBlock>), blocks(kTokenBlock), dim3(256), kTokenBlock * le_bytes, st, r, w_out, b_out, sh.L, sh.E, sh.top_k, N, ids, alpha); break;
+        case 2: hipLaunchKernelGGL((hash_heads<C, 2>), blocks(2), dim3(256), 2 * le_bytes, st, r, w_out, b_out, sh.L, sh.E, sh.top_k, N, ids, alpha); break;
+        default: hipLaunchKernelGGL((hash_heads<C, 1>), blocks(1), dim3(256), le_bytes, st, r, w_out, b_out, sh.L, sh.E, sh.top_k, N, ids, alpha); break;
+    }
     return (int)hipGetLastError();
 }
 

@@ -47,6 +47,14 @@ def run_hash(cfg, params, x_bits, n_seq, T):
     (256, 128, 2, 16, 3, 3, 70),
     (768, 128, 6, 128, 1, 2, 128),
     (768, 128, 6, 128, 3, 1, 200),
+    # the dense stages take blocks of 8 tokens from 4096 tokens up and of 2 from 1024 up (ragged last block) ...
+    (256, 128, 2, 16, 1, 33, 125),
+    (64, 64, 2, 8, 2, 9, 115),
+    # ... unless the inputs / logits of a block would not fit the LDS budget: 8 -> 2, 2 -> 1
+    (2056, 64, 1, 4, 1, 33, 125),
+    (6400, 64, 1, 4, 1, 9, 115),
+    (64, 64, 9, 256, 2, 33, 125),
+    (64, 64, 30, 256, 1, 9, 115),
 ])
 def test_hash_forward_against_oracle(d, C, L, E, k, n_seq, T):
     say(f"hash function d={d} C={C} L={L} E={E} k={k} sequences={n_seq} x {T}")
@@ -106,6 +114,7 @@ def test_hash_argument_errors():
         assert sm.hash_param_count(bad) == 0
         with pytest.raises(sm.SidaError):
             sm.hash_forward(bad, t, t, 1, 4, t, t, t, None)
+    assert sm.hash_param_count(sm.SidaHashConfig(68, 64, 1, 4, 1, 8)) == 0          # d_model not a multiple of 8
     ok = sm.SidaHashConfig(64, 64, 1, 4, 1, 8)
     with pytest.raises(sm.SidaError):                     # sequence longer than configured
         sm.hash_forward(ok, t, t, 1, 9, t, t, t, None)
