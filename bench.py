@@ -194,7 +194,7 @@ def hash_leg(wl, C=128, seq_len=128):
             st.synchronize()
             dt = (time.perf_counter() - t0) / 20
         rows.append({"sequences": n_seq, "seq_len": seq_len, "ms": 1e3 * dt, "tokens_per_s": n / dt})
-    return {"config": {"d_model": wl.d_model, "C": C, "L": wl.L, "E": wl.E, "top_k": 1}, "rows": rows}
+    return {"config": {"d": wl.d_model, "C": C, "L": wl.L, "E": wl.E, "top_k": 1}, "rows": rows}
 
 
 def main():
@@ -390,7 +390,7 @@ def main():
         "ms_per_step": 1e3 * main["dt"] / main_steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "L": wl.L, "E": wl.E, "d_model": wl.d_model, "d_ff": wl.d_ff,
+        "config": {"workload": wl.name, "L": wl.L, "E": wl.E, "d": wl.d_model, "F": wl.d_ff,
                    "T": wl.T, "ids": f"zipf(s={wl.zipf_s})" if wl.zipf_s else "uniform",
                    "pool_slots": wl.S if main_mode == "streaming" else wl.L * wl.E,
                    "wave_experts": wl.W if main_mode == "streaming" else wl.E, "mode": main_mode},
