@@ -31,14 +31,14 @@ H2D_PEAK_GBS = 64.0            # PCIe Gen5 x16, one direction
 # Source: profiles/grouped_ffn_switch-base-128.hbm_traffic.txt
 # key: (workload name, mode, kernel) -> bytes per launch (fetch + write).
 MEASURED_TRAFFIC = {
-    ("switch-base-128-T16384", "resident", "gemm1"): (384175.2 * 2.0 + 98879.0) * 1024,
-    ("switch-base-128-T16384", "resident", "gemm2"): (427057.0 * 2.0 + 24962.6) * 1024,
-    ("switch-base-128-T16384", "resident_fused", "gemm1"): (383980.9 * 2.0 + 98881.7) * 1024,
-    ("switch-base-128-T16384", "resident_fused", "gemm2"): (429427.6 * 2.0 + 24976.1) * 1024,
-    ("switch-base-128-T16384", "streaming", "gemm1"): (54619.5 * 2.0 + 12370.9) * 1024,
+    ("switch-base-128-T16384", "resident", "gemm1"): (384017.7 * 2.0 + 98882.6) * 1024,
+    ("switch-base-128-T16384", "resident", "gemm2"): (426708.8 * 2.0 + 24960.4) * 1024,
+    ("switch-base-128-T16384", "resident_fused", "gemm1"): (383899.8 * 2.0 + 98874.7) * 1024,
+    ("switch-base-128-T16384", "resident_fused", "gemm2"): (430459.9 * 2.0 + 24980.5) * 1024,
+    ("switch-base-128-T16384", "streaming", "gemm1"): (54621.1 * 2.0 + 12370.4) * 1024,
     # launches with 128 x 128 and with 128 x 256 tiles over the 2+1 steps of the counter run: weighted mean
     ("switch-base-128-T16384", "streaming", "gemm2"): ((62001.6 * 126 + 95655.1 * 18) / 144 * 2.0
-                                                       + (1928.6 * 126 + 11584.7 * 18) / 144) * 1024,
+                                                       + (1928.6 * 126 + 11587.0 * 18) / 144) * 1024,
 }
 
 
