@@ -169,7 +169,7 @@ def serve_leg(wl, hw, S, W, policy, look, n_batches, warm, T_b):
 
 
 def hash_leg(wl, C=128, seq_len=128):
-    """Times sida_hash_forward (Section 3.2.2) with random parameters on 1, 8 and 64 sequences."""
+    """Times sida_hash_forward (Section 3.4.2) with random parameters on 1, 8 and 64 sequences."""
     import numpy as np
     import torch
     from paper_2310_18859_amd.binding import SidaHashConfig, hash_forward, hash_param_count, hash_workspace_bytes

@@ -3,7 +3,7 @@
  * The library serves one sparse Mixture-of-Experts layer at a time the way the paper's inference
  * thread does (Section 3.1; Algorithm 1, left column): the expert id and the scaling factor
  * alpha of every token come from a table that was built ahead of time (the "hash table" H[l][s]),
- * routers take no part, only experts that have tokens are invoked (Section 2.2), and only the
+ * routers take no part, only experts that have tokens are invoked (Section 2.3), and only the
  * experts a batch activates are kept in GPU memory, in a pool of S equal-sized slots that is
  * filled from host memory and replaced first-in-first-out (Section 3.1, Section 4.3).
  *
@@ -20,9 +20,13 @@
  *        W_in  bf16 [d_ff, d_model]   (row j = weights of hidden unit j), immediately followed by
  *        W_out bf16 [d_model, d_ff].
  *    Slot s of the pool is the byte range [s*expert_bytes, (s+1)*expert_bytes).
- *  - Every function returns SIDA_OK (0) or a negative sida_status.  On an error nothing has been
- *    enqueued and no bookkeeping has changed.  Faults of work that was already enqueued show up
- *    at the caller's next stream synchronisation, as with any HIP work.
+ *  - Every function returns SIDA_OK (0) or a negative sida_status.  Arguments and state are
+ *    checked before anything else: on SIDA_EINVAL, SIDA_ENOSPC, SIDA_ESTATE, SIDA_ENOMEM,
+ *    SIDA_EAGAIN and SIDA_ECLOSED nothing has been enqueued and no bookkeeping has changed.
+ *    SIDA_EHIP means a HIP call failed part-way: launches and copies enqueued before it stay
+ *    enqueued and the waves they belong to count as prefetched / forwarded; drain the streams and
+ *    call sida_pool_reset() before using the context again.  Faults of work that was already
+ *    enqueued show up at the caller's next stream synchronisation, as with any HIP work.
  *  - A context is not thread-safe (the hash-table queue calls excepted); use one per serving thread.  All compute of one context must
  *    be enqueued on one stream, all copies on one (other) stream.
  *  - Limits: 1 <= E <= SIDA_MAX_E; d_model and d_ff multiples of 128; 1 <= W <= S.
@@ -71,8 +75,8 @@ typedef struct sida_config {
     int32_t max_T;    /* most tokens per layer call                                          */
 } sida_config;
 
-/* Residency plan of one layer for one batch: the outcome of Algorithm 1's loop "for each token:
- * check its expert; if it is not on the GPU, move it there" under the FIFO budget.  Plain data,
+/* Residency plan of one layer for one batch: the outcome of Algorithm 1's inference-thread loop
+ * (every token's expert is checked and moved to the GPU when it is not there) under the FIFO budget.  Plain data,
  * owned by the caller, filled by sida_moe_plan().  Arrays indexed by expert id hold -1 for
  * experts without tokens (they are never loaded nor invoked).  Waves carry a global index that
  * counts up over the life of the pool; a layer's waves are first_wave .. first_wave+n_waves-1. */
@@ -205,7 +209,8 @@ int sida_queue_push(sida_ctx *ctx, int64_t tag, const int32_t *ids_host, int32_t
 int sida_queue_close(sida_ctx *ctx);
 /* Tables waiting (>= 0), or a negative status. */
 int sida_queue_size(sida_ctx *ctx);
-/* Waits up to timeout_ms for a table ("remains idle if H_i is not found", Section 3.1), removes
+/* Waits up to timeout_ms for a table (Section 3.1: the inference thread idles while its table is
+ * missing), removes
  * the oldest one and plans its L layers in order, exactly as L calls of sida_moe_plan_lookahead
  * would: plans[L] (caller's array) are then run with sida_run_layers.  tag / T may be NULL.
  * SIDA_EAGAIN on timeout, SIDA_ECLOSED when closed and empty; the pool bookkeeping is untouched
@@ -215,8 +220,8 @@ int sida_queue_pop_plan(sida_ctx *ctx, int32_t timeout_ms, int64_t *tag, int32_t
 /* expert_prefetch(slot_table, host_weights, stream): enqueues, on copy_stream, the host -> pool
  * copies of the experts that local wave `wave` of `plan` misses (one copy of expert_bytes each),
  * after making copy_stream wait for the compute of wave_dep[wave] — the last wave that read a
- * slot about to be overwritten.  This is the "load the activated experts ahead of the forward
- * pass, overlapped with the previous compute" step of Section 3.1.
+ * slot about to be overwritten.  This is the step of Section 3.1 that loads the activated experts ahead of
+ * the forward pass, overlapped with the previous compute.
  * Waves must be prefetched in global order; a wave that was already prefetched is a no-op (0).
  * SIDA_ESTATE if an earlier wave has not been prefetched yet, or if the forward call of
  * wave_dep[wave] has not been enqueued yet (the wait could not be expressed). */
@@ -242,7 +247,8 @@ int sida_moe_layer_forward(sida_ctx *ctx, const sida_plan *plan, const void *x_d
 
 /* Experts per token, 1..SIDA_MAX_TOP_K (default 1 = Switch routing).  Eq. 1 of Section 2.1 with a
  * selected set of k experts: y[t,:] = sum_{j<k} alpha[t,j] * f_{ids[t,j]}(x[t,:]); the paper
- * evaluates with the hash function's top-3 experts on two of its datasets (Section 4.1).
+ * evaluates with the hash function's top-3 experts on two of its datasets (Section 4, hyperparameters;
+ * top-3 hit rates in Section 4.6).
  * With k > 1 every "T" of the plan, forward and stage calls counts (token, expert) PAIRS:
  * ids and alpha are [tokens, k] row-major (T = tokens*k entries, T <= max_T, T % k == 0,
  * SIDA_EINVAL otherwise), x and y keep one row per token (T/k rows).  The pairs are sorted and
@@ -286,7 +292,7 @@ int sida_grouped_ffn(sida_ctx *ctx, const sida_plan *plan, int32_t wave, void *w
 int sida_combine(sida_ctx *ctx, const float *alpha_dev, int32_t T, void *y_dev,
                  void *workspace_dev, size_t workspace_bytes, void *stream);
 
-/* ---- the hash function of the hash-building thread (Section 3.2.2) ----------------------------
+/* ---- the hash function of the hash-building thread (Section 3.4.2) ----------------------------
  * Predicts the hash table of a batch from the token embeddings alone: for every token and MoE
  * layer the top_k experts and their scaling factors.  Network: a fully connected layer that
  * compresses the embedding to C values, a 2-layer LSTM of width C over the sequence, attention of
@@ -319,6 +325,20 @@ size_t sida_hash_workspace_bytes(const sida_hash_config *cfg, int32_t n_tokens);
 int sida_hash_forward(const sida_hash_config *cfg, const float *params_dev, const void *x_dev, int32_t n_seq,
                       int32_t seq_len, int32_t *ids_dev, float *alpha_dev, void *workspace_dev,
                       size_t workspace_bytes, void *stream);
+
+/* sida_hash_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels,
+ * same results; the intermediates (8*C floats per token) live in a statically allocated device
+ * array of SIDA_HASH_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the
+ * process ends.  Calls neither hipMalloc / hipFree nor any other allocating routine; the first
+ * call on a device looks the array's address up.  n_seq * seq_len tokens whose intermediates do not
+ * fit (more than 4095 tokens at C = 128, 8191 at C = 64) -> SIDA_ENOSPC, nothing enqueued.
+ * All calls on one GPU share that GPU's array (it keeps the last call's contents, and nothing in
+ * it needs clearing): calls that overlap in time on one GPU - on different streams or from
+ * different threads - race; order them on one stream or with events. */
+#define SIDA_HASH_STATIC_SCRATCH_BYTES (16u << 20)
+int sida_hash_forward_static(const sida_hash_config *cfg, const float *params_dev, const void *x_dev, int32_t n_seq,
+                             int32_t seq_len, int32_t *ids_dev, float *alpha_dev, void *stream);
 
 /* Inspection: the order in which a grouped-GEMM launch walks its output tiles.  For a launch over
  * m_tiles token tiles (the first m_tall of them belonging to experts with more than one tile) and

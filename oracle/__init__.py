@@ -7,7 +7,7 @@ Floating point: see ``sida_oracle.c`` (Eq. 1 of Section 2.1 with top-1 selection
 scaling factor looked up per token as in Section 3.1).  Integer parts, all plain Python loops:
 
 * ``token_counts`` / ``stable_order``: the grouping of tokens by expert that any "invoke only the
-  experts that have tokens" implementation (Section 2.2) needs.  The paper prescribes no order,
+  experts that have tokens" implementation (Section 2.3) needs.  The paper prescribes no order,
   so the only order that is unique is used: by expert id, ties by token index.
 * ``PoolState.plan_layer``: the inference thread's residency step of Algorithm 1 ("for each
   MoE layer and each token: check the expert; if it is not on the GPU, move it there") under a

@@ -1,4 +1,4 @@
-"""CPU oracle of the hash function that predicts expert ids and scaling factors (Section 3.2.2).
+"""CPU oracle of the hash function that predicts expert ids and scaling factors (Section 3.4.2).
 TEST INFRASTRUCTURE ONLY, like the rest of this package.
 
 The paper describes the network in words: a fully connected layer that compresses the embedding
@@ -21,7 +21,9 @@ leaves open is a reading, stated here and in the design notes:
 
 All arithmetic in float64, steps in the order above, no fusion.
 Pins: tests/test_oracle_hash.py (SparseMax against an exhaustive search over supports and against
-its defining properties; the LSTM against torch.nn.LSTM; hand cases)."""
+its defining properties; the LSTM against torch.nn.LSTM; the attention against hand-worked
+sequences - one-hot weights for well separated rows, the plain mean for a zero query, a
+two-token case from tests/golden/sparse_attention_2tok.txt; special cases of the whole forward)."""
 from __future__ import annotations
 
 import numpy as np
@@ -62,6 +64,20 @@ def lstm_layer(x, w_ih, w_hh, b_ih, b_hh) -> np.ndarray:
     return out
 
 
+def sparse_attention(h) -> np.ndarray:
+    """Attention of a sequence over itself with SparseMax weights (Section 3.4.2): query = key =
+    value = h [T, C]; for token t the scores are the plain dot products h[u] . h[t] over the
+    positions u of the sequence, the weights their SparseMax, the output the weighted sum of the
+    rows h[u].  Returns [T, C]."""
+    h = np.asarray(h, dtype=np.float64)
+    out = np.empty_like(h)
+    for t in range(h.shape[0]):
+        scores = np.array([np.dot(h[u], h[t]) for u in range(h.shape[0])])
+        w = sparsemax(scores)
+        out[t] = sum(w[u] * h[u] for u in range(h.shape[0]))
+    return out
+
+
 def param_shapes(d_model: int, C: int, L: int, E: int):
     """Names and shapes of the parameters, in the order they are packed for the library."""
     return [("w_in", (C, d_model)), ("b_in", (C,)),
@@ -79,10 +95,7 @@ def hash_forward(params: dict, x, L: int, E: int, k: int):
     c0 = x @ p["w_in"].T + p["b_in"]                                     # compress the embedding
     h1 = lstm_layer(c0, p["w_ih1"], p["w_hh1"], p["b_ih1"], p["b_hh1"])
     h2 = lstm_layer(h1, p["w_ih2"], p["w_hh2"], p["b_ih2"], p["b_hh2"])
-    att = np.empty_like(h2)
-    for t in range(T):                                                   # sparse attention over the sequence
-        w = sparsemax(h2 @ h2[t])
-        att[t] = w @ h2
+    att = sparse_attention(h2)                                           # over the sequence
     r = att + c0                                                         # residual before the last layer
     logits = r @ p["w_out"].T + p["b_out"]
     ids = np.empty((L, T, k), dtype=np.int32)

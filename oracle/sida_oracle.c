@@ -72,7 +72,7 @@ int sida_oracle_moe_forward(const uint16_t *x, const int32_t *ids, const float *
 }
 
 /* Eq. 1 of Section 2.1 with a selected set I of k experts per token (the paper evaluates with the
- * top-3 experts of the hash function on two of its datasets, Section 4.1):
+ * top-3 experts of the hash function on two of its datasets, Section 4, hyperparameters):
  *
  *     y[t,c] = sum_{j<k} alpha[t,j] * ( W_out[e] relu(W_in[e] x_t) )[c],      e = ids[t,j]
  *

@@ -5,5 +5,5 @@ There is no CPU fallback: importing this package without the built library raise
 from .binding import (  # noqa: F401
     SIDA_MAX_E, K_NAMES, Context, SidaError, SidaPlan, SidaConfig, WsLayout, lib, lib_path,
     streams_create, streams_destroy, tile_order, SidaHashConfig, hash_param_count, hash_workspace_bytes,
-    hash_forward,
+    hash_forward, hash_forward_static,
 )

@@ -84,6 +84,7 @@ def lib():
         "sida_hash_param_count": (sz, [C.POINTER(SidaHashConfig)]),
         "sida_hash_workspace_bytes": (sz, [C.POINTER(SidaHashConfig), i32]),
         "sida_hash_forward": (C.c_int, [C.POINTER(SidaHashConfig), vp, vp, i32, i32, vp, vp, vp, sz, vp]),
+        "sida_hash_forward_static": (C.c_int, [C.POINTER(SidaHashConfig), vp, vp, i32, i32, vp, vp, vp]),
         "sida_streams_create": (C.c_int, [i32, C.POINTER(vp), C.POINTER(vp)]),
         "sida_streams_destroy": (C.c_int, [vp, vp]),
         "sida_set_top_k": (C.c_int, [vp, i32]),
@@ -150,6 +151,13 @@ def hash_forward(cfg: SidaHashConfig, params, x, n_seq, seq_len, ids, alpha, wor
                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc:
         raise SidaError(rc, "sida_hash_forward")
+
+
+def hash_forward_static(cfg: SidaHashConfig, params, x, n_seq, seq_len, ids, alpha, stream):
+    rc = lib().sida_hash_forward_static(C.byref(cfg), _ptr(params), _ptr(x), n_seq, seq_len, _ptr(ids), _ptr(alpha),
+                                        _stream(stream))
+    if rc:
+        raise SidaError(rc, "sida_hash_forward_static")
 
 
 def streams_create(copy_cus: int):

@@ -32,8 +32,18 @@ int make_events(sida_ctx *c)
     c->ev_done.assign(kEventRing, nullptr);
     c->ready_recorded.assign(kEventRing, 0);
     for (int i = 0; i < kEventRing; ++i) {
-        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming));
+        hipError_t e = hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) {                                // give back what was made: a later call starts over
+            for (int j = 0; j <= i; ++j) {
+                if (c->ev_ready[j]) (void)hipEventDestroy(c->ev_ready[j]);
+                if (c->ev_done[j]) (void)hipEventDestroy(c->ev_done[j]);
+            }
+            c->ev_ready.clear();
+            c->ev_done.clear();
+            c->last_hip = (int)e;
+            return SIDA_EHIP;
+        }
     }
     c->events_made = true;
     return SIDA_OK;
@@ -420,6 +430,7 @@ int sida_create(const sida_config *cfg, sida_ctx **out)
         c->touched_at.assign(cfg->S, -1);
         c->key_slot.assign((size_t)cfg->L * cfg->E, -1);
         c->next_use.reserve((size_t)cfg->L * cfg->E);
+        c->wave_mark.assign(cfg->S, -1);
     } catch (const std::bad_alloc &) {
         delete c;
         return SIDA_ENOMEM;
@@ -598,7 +609,11 @@ int sida_moe_plan(sida_ctx *c, int32_t layer, const int32_t *ids_host, int32_t T
     if (!c || !out || layer < 0 || layer >= c->cfg.L || T < 0 || T > c->cfg.max_T || (T > 0 && !ids_host))
         return SIDA_EINVAL;
     if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E) return SIDA_ESTATE;   // wave counter exhausted: reset the pool
-    return plan_layer(c, layer, ids_host, T, nullptr, 0, out);
+    try {
+        return plan_layer(c, layer, ids_host, T, nullptr, 0, out);
+    } catch (const std::bad_alloc &) {
+        return SIDA_ENOMEM;
+    }
 }
 
 int sida_moe_plan_lookahead(sida_ctx *c, int32_t layer, const int32_t *ids_host, int32_t T,
@@ -701,32 +716,35 @@ int sida_queue_pop_plan(sida_ctx *c, int32_t timeout_ms, int64_t *tag, int32_t *
     if (c->next_wave > INT32_MAX - 2 * SIDA_MAX_E * L) return SIDA_ESTATE;
     QueuedTable q;
     std::vector<int32_t> behind;                      // activated keys of the batches still queued
+    std::vector<int32_t> future;
     try {
         std::unique_lock<std::mutex> lk(c->q_mu);
         if (!c->q_cv.wait_for(lk, std::chrono::milliseconds(timeout_ms),
                               [&] { return !c->queue.empty() || c->q_closed; }))
             return SIDA_EAGAIN;                       // the inference thread stays idle (Section 3.1)
         if (c->queue.empty()) return SIDA_ECLOSED;
-        q = std::move(c->queue.front());
-        c->queue.pop_front();
+        // Everything that allocates happens while the table is still queued: a failure leaves
+        // the queue and the pool bookkeeping as they were.
         if (c->policy == SIDA_POLICY_BELADY) {
             int32_t n = 0;
-            for (const QueuedTable &o : c->queue) {
+            for (auto it = c->queue.begin() + 1; it != c->queue.end(); ++it) {
                 if (n++ == c->lookahead) break;
-                behind.insert(behind.end(), o.keys.begin(), o.keys.end());
+                behind.insert(behind.end(), it->keys.begin(), it->keys.end());
             }
         }
-        lk.unlock();
-        std::vector<int32_t> future;
-        for (int32_t l = 0; l < L; ++l) {
-            future.assign(q.keys.begin() + q.key_begin[l + 1], q.keys.end());   // later layers of this batch
-            future.insert(future.end(), behind.begin(), behind.end());
-            const int rc = plan_layer(c, l, q.ids.data() + (size_t)l * q.T, q.T, future.data(), (int64_t)future.size(),
-                                      &plans[l]);
-            if (rc != SIDA_OK) return rc;             // cannot happen: ids were checked when pushed
-        }
+        future.reserve(c->queue.front().keys.size() + behind.size());
+        q = std::move(c->queue.front());              // moving a QueuedTable does not allocate
+        c->queue.pop_front();
     } catch (const std::bad_alloc &) {
         return SIDA_ENOMEM;
+    }
+    for (int32_t l = 0; l < L; ++l) {                 // within the reserved capacity: no allocation
+        future.assign(q.keys.begin() + q.key_begin[l + 1], q.keys.end());   // later layers of this batch
+        future.insert(future.end(), behind.begin(), behind.end());
+        const int rc = plan_layer(c, l, q.ids.data() + (size_t)l * q.T, q.T, future.data(), (int64_t)future.size(),
+                                  &plans[l]);
+        if (rc != SIDA_OK) return rc;                 // cannot happen: ids were checked when pushed, and the
+                                                      // planner allocates nothing
     }
     if (tag) *tag = q.tag;
     if (T) *T = q.T;
@@ -855,6 +873,24 @@ int sida_hash_forward(const sida_hash_config *h, const float *params_dev, const 
     const HashShape sh{h->d_model, h->C, h->L, h->E, h->top_k};
     const int rc = launch_hash_forward(sh, params_dev, x_dev, n_seq, seq_len, ids_dev, alpha_dev,
                                        static_cast<float *>(workspace_dev), static_cast<hipStream_t>(stream));
+    return rc == 0 ? SIDA_OK : SIDA_EHIP;
+}
+
+int sida_hash_forward_static(const sida_hash_config *h, const float *params_dev, const void *x_dev, int32_t n_seq,
+                             int32_t seq_len, int32_t *ids_dev, float *alpha_dev, void *stream)
+{
+    static_assert(kHashStaticScratchBytes == SIDA_HASH_STATIC_SCRATCH_BYTES, "header and library agree on the limit");
+    if (!hash_cfg_ok(h) || n_seq < 0 || seq_len < 0 || seq_len > h->max_seq_len) return SIDA_EINVAL;
+    if ((int64_t)n_seq * seq_len > INT32_MAX / 8) return SIDA_EINVAL;
+    if (n_seq == 0 || seq_len == 0) return SIDA_OK;
+    if (!params_dev || !x_dev || !ids_dev || !alpha_dev) return SIDA_EINVAL;
+    if (sida_hash_workspace_bytes(h, n_seq * seq_len) > kHashStaticScratchBytes) return SIDA_ENOSPC;
+    float *ws = nullptr;
+    if (hash_static_scratch(&ws) != 0) return SIDA_EHIP;
+    const HashShape sh{h->d_model, h->C, h->L, h->E, h->top_k};
+    // every intermediate is written before it is read: nothing in the scratch has to start at zero
+    const int rc = launch_hash_forward(sh, params_dev, x_dev, n_seq, seq_len, ids_dev, alpha_dev, ws,
+                                       static_cast<hipStream_t>(stream));
     return rc == 0 ? SIDA_OK : SIDA_EHIP;
 }
 

@@ -54,6 +54,7 @@ struct sida_ctx {
     std::vector<int64_t> loaded_at;    // [S] clock of the load that filled the slot
     std::vector<int64_t> touched_at;   // [S] clock of the slot's last load or hit
     std::vector<int64_t> next_use;     // [L*E] scratch of the planner
+    std::vector<int32_t> wave_mark;    // [S] scratch of the planner: slots of the wave being assembled
     int32_t next_wave = 0;             // next global wave index to hand out
     uint32_t epoch = 1;
 

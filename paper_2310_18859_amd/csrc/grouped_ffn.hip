@@ -4,7 +4,7 @@
 //     h      = relu(x_perm_e * W_in[e]^T)      (GEMM 1, [rows, d] x [F, d]^T, ReLU, bf16 out)
 //     y_perm = h * W_out[e]^T                  (GEMM 2, [rows, F] x [d, F]^T, bf16 out)
 // which is the expert MLP f_i of Eq. 1 (Section 2.1) invoked only for experts that have tokens
-// (Section 2.2).  Expert weights are read from the pool slot named by the wave table.
+// (Section 2.3).  Expert weights are read from the pool slot named by the wave table.
 //
 // Both GEMMs are "NT": activations [M,K] and weights [N,K] are K-contiguous, so every MFMA
 // operand fragment (8 consecutive K values of one row) is one 16-byte access.

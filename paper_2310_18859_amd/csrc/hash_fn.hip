@@ -1,4 +1,4 @@
-// The hash function of the hash-building thread (Section 3.2.2): predicts, for every token of a
+// The hash function of the hash-building thread (Section 3.4.2): predicts, for every token of a
 // sequence and every MoE layer, the experts to activate and their scaling factors, from the token
 // embeddings alone - a fully connected layer that compresses the embedding, a 2-layer LSTM, an
 // attention layer over the LSTM's output sequence whose weights go through SparseMax, a residual
@@ -17,12 +17,23 @@
 #include <hip/hip_runtime.h>
 
 #include <cfloat>
+#include <mutex>
 
 #include "kernels.h"
 
 namespace sida {
 
 namespace {
+
+// Scratch of sida_hash_forward_static: the intermediates of one call (8*C floats per token) live
+// here instead of in a caller's workspace.  Every GPU the library runs on holds its own copy of
+// the array, at its own address, until the process ends.  In host code the array's name is only a
+// stand-in for the symbol: the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[kHashStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float *g_scratch_ptr[kMaxDevices] = {};
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
@@ -325,6 +336,24 @@ int run(const HashShape &sh, const float *p, const void *x, int n_seq, int T, in
 }
 
 }  // namespace
+
+int hash_static_scratch(float **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // the current device's copy of the array
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return 0;
+}
 
 int launch_hash_forward(const HashShape &sh, const float *params, const void *x, int32_t n_seq, int32_t seq_len,
                         int32_t *ids, float *alpha, float *ws, hipStream_t st)

@@ -83,6 +83,10 @@ struct HashShape {
 };
 int launch_hash_forward(const HashShape &sh, const float *params, const void *x, int32_t n_seq, int32_t seq_len,
                         int32_t *ids, float *alpha, float *ws, hipStream_t st);
+// Device address of the current device's statically allocated hash-function scratch
+// (kHashStaticScratchBytes bytes, 256-byte aligned); looked up once per device.  Returns a hipError_t.
+constexpr size_t kHashStaticScratchBytes = size_t(16) << 20;
+int hash_static_scratch(float **out);
 
 constexpr int kGemmSinkBytes = 64 * 1024;
 constexpr int kGemmTileM = 128;   // token rows per GEMM tile of large launches

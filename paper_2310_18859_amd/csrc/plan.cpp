@@ -64,11 +64,12 @@ int plan_layer(sida_ctx *c, int32_t layer, const int32_t *ids, int32_t T, const 
         return later[key] == kNever ? kNever : p.n_active + later[key];
     };
 
-    // Everything below works on the context's vectors directly; nothing can fail from here on.
+    // Everything below works on the context's vectors directly and allocates nothing: it cannot fail.
     int32_t g = c->next_wave;
     p.first_wave = g;
     int32_t in_wave = 0;              // experts already placed in wave g
-    std::vector<int32_t> used(S, -1); // used[s] == g  <=>  slot s belongs to the current wave
+    std::vector<int32_t> &used = c->wave_mark;   // [S], sized when the context was made:
+    std::fill(used.begin(), used.end(), -1);     // used[s] == g  <=>  slot s belongs to the current wave
     int32_t dep = -1;
     auto close_wave = [&]() {
         p.wave_dep[g - p.first_wave] = dep;

@@ -1,6 +1,6 @@
 // K-a: token -> expert stable counting sort and permute-gather.
 //
-// Any implementation that invokes only the experts that have tokens (Section 2.2) must bring the
+// Any implementation that invokes only the experts that have tokens (Section 2.3) must bring the
 // rows of one expert together.  The order is fixed as (expert id, token index) so that the result
 // is unique: perm[offsets[e] + j] is the j-th smallest token index routed to expert e.
 //

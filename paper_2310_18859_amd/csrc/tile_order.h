@@ -3,7 +3,7 @@
 // a bijection without a GPU.
 #pragma once
 
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 #define SIDA_HD __host__ __device__ __forceinline__
 #else
 #define SIDA_HD inline

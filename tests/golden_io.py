@@ -70,3 +70,19 @@ def read_table2():
             name, model, moe, pct = line.split()
             rows[name] = (float(model), float(moe), float(pct))
     return rows
+
+
+def read_attention_cases(name="sparse_attention_2tok.txt"):
+    """Returns {case: (h rows, out rows)} as lists of lists of floats."""
+    cases, cur = {}, None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, _, v = line.partition(" ")
+            if k == "case":
+                cur = cases.setdefault(v, ([], []))
+            else:
+                cur[0 if k == "h" else 1].append([float(t) for t in v.split()])
+    return cases

@@ -2,7 +2,8 @@
 (sida_run_layers over all layers, pool and wave sizes of the workload): integer results of every
 layer bit-exact against numpy's stable sort (which the oracle is pinned to), plans against the
 oracle's planner, and y on sampled tokens against the oracle (a token's output does not depend on
-the other tokens, so sampled rows can be computed one by one)."""
+the other tokens, so sampled rows can be computed one by one), plus every row of one layer per
+workload."""
 import numpy as np
 import pytest
 import torch
@@ -16,7 +17,7 @@ pytestmark = pytest.mark.gpu
 SAMPLES = 96     # tokens per layer checked against the oracle (plus every token of the smallest experts)
 
 
-def check_workload(wl, layers_checked):
+def check_workload(wl, layers_checked, whole_layer=0):
     say(f"full-size parity: {wl.name}  L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T} S={wl.S} W={wl.W}")
     r = make_runner(wl)
     say("  host weights ready")
@@ -39,6 +40,10 @@ def check_workload(wl, layers_checked):
                 continue
             y = bf16_tensor_to_f32(dev[l][3])
             assert np.isfinite(y).all()
+            if l == whole_layer and rep == 1:             # every row of one layer, in the pool's steady state
+                ref = oracle_layer(wl, r, l, x_bits, ids, alpha)
+                worst = max(worst, assert_close(y, ref, f"{wl.name} rep {rep} layer {l} (all rows)"))
+                continue
             rng = np.random.default_rng(1000 * rep + l)
             counts = np.bincount(ids, minlength=wl.E)
             rare = np.argsort(counts)[:2]                 # the two least popular experts, all their tokens

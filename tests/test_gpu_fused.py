@@ -63,7 +63,7 @@ def test_fused_equals_separate_passes_bit_for_bit(name, L, E, d, F, T, zipf, S, 
     rb.close()
 
 
-def test_fused_paper_shape_streaming_and_resident():
+def test_fused_paper_shape_streaming():
     """Switch-base-128 shape at full T: two layers streamed through the 32-slot pool (eight waves
     each), fused against separate passes bit for bit, sampled rows against the oracle."""
     wl = WORKLOADS[2].scaled(L=2)

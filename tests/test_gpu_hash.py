@@ -1,4 +1,4 @@
-"""GPU parity of the hash function (Section 3.2.2) against its float64 oracle: scaling factors
+"""GPU parity of the hash function (Section 3.4.2) against its float64 oracle: scaling factors
 within a tolerance; expert ids as a valid choice (the k most probable experts by the oracle's own
 probabilities, up to that tolerance at near-ties); then the predicted table drives a MoE layer."""
 import numpy as np

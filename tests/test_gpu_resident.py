@@ -1,0 +1,107 @@
+"""GPU parity in the launch configuration bench.py's `resident` legs time: a pool of L*E slots and
+waves of E experts, so that after a first pass every expert is a hit and each GEMM of a layer is ONE
+launch over all activated experts (128 or 256 of them, a few hundred token tiles of both kinds -
+experts with thousands of tokens beside experts with a few dozen).  Whole layers, every row,
+against the oracle; the separate-pass path, the fused path and three experts per token."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_close, bf16_tensor_to_f32, layer_inputs, oracle_layer, say
+from paper_2310_18859_amd.runner import MoERunner
+from workloads import WORKLOADS, fill_host_weights, gen_gate, gen_ids, gen_x
+
+pytestmark = pytest.mark.gpu
+
+
+def resident_runner(wl):
+    """As bench.py builds its resident runner."""
+    r = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.L * wl.E, wl.E, wl.T)
+    fill_host_weights(wl, r.alloc_host_weights())
+    assert r.copy_cus == 0                                 # every compute unit for the GEMMs
+    return r
+
+
+def run_pass(r, ins):
+    plans = r.plan_all([i[1] for i in ins])
+    dev = [r.to_device(*i) for i in ins]
+    for d in dev:
+        d[3].fill_(7.0)                                    # every row of y must be overwritten
+    torch.cuda.synchronize()
+    r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
+    r.sync()
+    return plans, dev
+
+
+def check_sort(r, wl, ids, T):
+    """The sort left in the workspace by the last layer of a pass: bit-exact."""
+    perm = np.argsort(ids, kind="stable").astype(np.int32)
+    inv = np.empty(T, np.int32)
+    inv[perm] = np.arange(T, dtype=np.int32)
+    assert np.array_equal(r.region(T, "counts", torch.int32, (wl.E,)).cpu().numpy(), np.bincount(ids, minlength=wl.E))
+    assert np.array_equal(r.region(T, "perm", torch.int32, (T,)).cpu().numpy(), perm)
+    assert np.array_equal(r.region(T, "inv", torch.int32, (T,)).cpu().numpy(), inv)
+
+
+def check_resident(wl, whole_layers, with_top_k=False):
+    say(f"resident launch shape: {wl.name} L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T}, pool of {wl.L * wl.E} slots")
+    r = resident_runner(wl)
+    say("  host weights ready")
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    plans, _ = run_pass(r, ins)                            # loads every activated expert
+    assert all(p.n_waves == 1 for p in plans)
+    sample = np.arange(0, wl.T, 61)
+    outs = {}
+    for fused in (False, True):
+        r.ctx.set_fusion(fused)
+        plans, dev = run_pass(r, ins)
+        assert sum(p.n_miss for p in plans) == 0 and all(p.n_waves == 1 for p in plans)
+        check_sort(r, wl, ins[-1][1], wl.T)
+        worst = 0.0
+        for l in range(wl.L):
+            x_bits, ids, alpha = ins[l]
+            y = bf16_tensor_to_f32(dev[l][3])
+            assert np.isfinite(y).all()
+            if l in whole_layers[fused]:                   # every row of the layer
+                ref = oracle_layer(wl, r, l, x_bits, ids, alpha)
+                worst = max(worst, assert_close(y, ref, f"{wl.name} resident fused={fused} layer {l} (all rows)"))
+            else:
+                ref = oracle_layer(wl, r, l, x_bits, ids, alpha, rows=sample)
+                worst = max(worst, assert_close(y[sample], ref, f"{wl.name} resident fused={fused} layer {l}"))
+        outs[fused] = [d[3].view(torch.uint16).cpu().numpy() for d in dev]
+        say(f"  fused={fused}: all hits, worst rel err {worst:.3e}")
+    for l in range(wl.L):                                  # the two paths do the same arithmetic
+        assert np.array_equal(outs[False][l], outs[True][l]), f"layer {l}: fused != separate passes"
+    if with_top_k:                                         # as bench.py's top_k leg: T/3 tokens, 3 experts each
+        k, hw = 3, r.host_weights.numpy()
+        tok = wl.T // k
+        r.ctx.set_top_k(k)
+        ins_k = [(gen_x(wl, l, tok), gen_ids(wl, l, tok * k), gen_gate(wl, l, tok * k)) for l in range(wl.L)]
+        for fused in (False, True):
+            r.ctx.set_fusion(fused)
+            run_pass(r, ins_k)                             # may activate experts the top-1 ids did not
+            plans, dev = run_pass(r, ins_k)
+            assert sum(p.n_miss for p in plans) == 0
+            check_sort(r, wl, ins_k[-1][1], tok * k)
+            l = 1 if fused else 0                          # one whole layer per mode
+            x_bits, ids, alpha = ins_k[l]
+            ref = oracle.moe_forward_topk(x_bits, ids.reshape(tok, k), alpha.reshape(tok, k),
+                                          [hw[l * wl.E + e] for e in range(wl.E)], wl.d_model, wl.d_ff)
+            err = assert_close(bf16_tensor_to_f32(dev[l][3]), ref, f"{wl.name} resident top-{k} fused={fused} layer {l}")
+            say(f"  {k} experts per token, gather folded in={fused}: layer {l} all {tok} tokens, rel err {err:.3e}")
+        r.ctx.set_top_k(1)
+    r.close()
+
+
+def test_resident_switch_base_128():
+    check_resident(WORKLOADS[2], whole_layers={False: (0,), True: (3,)}, with_top_k=True)
+
+
+def test_resident_switch_base_256():
+    # two of the six layers: a layer's launches do not depend on how many layers share the pool
+    check_resident(WORKLOADS[3].scaled(L=2), whole_layers={False: (0,), True: (1,)})
+
+
+def test_resident_switch_large_128():
+    check_resident(WORKLOADS[4].scaled(L=2), whole_layers={False: (1,), True: (0,)})

@@ -1,4 +1,4 @@
-"""Pins for the oracle of the hash function (Section 3.2.2): SparseMax, the LSTM, the whole forward."""
+"""Pins for the oracle of the hash function (Section 3.4.2): SparseMax, the LSTM, the whole forward."""
 import itertools
 
 import numpy as np
@@ -110,3 +110,67 @@ def test_attention_on_a_one_token_sequence_returns_the_token():
     h2 = hash_fn.lstm_layer(h1, p["w_ih2"], p["w_hh2"], p["b_ih2"], p["b_hh2"])
     z = (h2 + c0) @ p["w_out"].T + p["b_out"]                             # sparsemax of one score is [1]
     np.testing.assert_allclose(probs[0], np.exp(z) / np.exp(z).sum(), atol=1e-12)
+
+
+# ---- the attention layer on sequences of more than one token -------------------------------------
+def test_attention_hand_worked_sequences():
+    from golden_io import read_attention_cases
+    cases = read_attention_cases()
+    assert set(cases) == {"two_tokens", "three_tokens"}
+    for name, (h, out) in cases.items():
+        np.testing.assert_allclose(hash_fn.sparse_attention(np.array(h)), np.array(out), atol=1e-14, err_msg=name)
+
+
+def test_attention_of_well_separated_rows_returns_each_row():
+    """Mutually orthogonal rows of squared length >= 1: a token's score with itself leads every
+    other score (all 0) by at least 1, so its SparseMax weights are one-hot and it gets its own row
+    back.  SoftMax weights, or scores divided by sqrt(C), would mix rows in."""
+    C = 6
+    h = np.zeros((4, C))
+    for t, (axis, length) in enumerate([(0, 1.0), (2, 1.2), (3, -1.5), (5, 3.0)]):
+        h[t, axis] = length
+    np.testing.assert_allclose(hash_fn.sparse_attention(h), h, atol=1e-15)
+    # the control: with squared lengths below 1 the other rows do get weight
+    assert np.abs(hash_fn.sparse_attention(0.5 * h) - 0.5 * h).max() > 0.05
+
+
+def test_attention_of_a_zero_query_is_the_mean_of_the_rows():
+    """A zero row scores 0 against every position: uniform weights 1/T, so its output is the plain
+    mean of the value rows (which must be the rows of h themselves, all T of them)."""
+    rng = np.random.default_rng(11)
+    h = rng.standard_normal((5, 3))
+    h[2] = 0.0
+    np.testing.assert_allclose(hash_fn.sparse_attention(h)[2], h.mean(axis=0), atol=1e-15)
+
+
+def test_attention_does_not_depend_on_the_order_of_the_other_tokens():
+    """Token t's output is a function of the set of rows: permuting the sequence permutes the outputs."""
+    rng = np.random.default_rng(12)
+    h = rng.standard_normal((7, 4)) * 0.8
+    perm = rng.permutation(7)
+    np.testing.assert_allclose(hash_fn.sparse_attention(h[perm]), hash_fn.sparse_attention(h)[perm], atol=1e-13)
+
+
+def test_forward_for_a_sequence_uses_the_attention_over_the_second_lstm_layer():
+    """Whole forward on T > 1 with an output layer that reads the residual sum back out: with
+    w_out = identity rows and b_out = 0 the logits ARE r = attention(h2) + c0, so
+    log(probs) differences recover r up to a constant per token."""
+    rng = np.random.default_rng(13)
+    d, C, T = 5, 4, 6
+    p = random_params(rng, d, C, 1, C, scale=0.6)
+    p["w_out"] = np.eye(C)
+    p["b_out"] = np.zeros(C)
+    x = rng.standard_normal((T, d))
+    _, _, probs = hash_fn.hash_forward(p, x, 1, C, 1)
+    c0 = x @ p["w_in"].T + p["b_in"]
+    ref = torch.nn.LSTM(C, C, num_layers=2, batch_first=True).double()
+    with torch.no_grad():
+        for n, key in (("weight_ih_l0", "w_ih1"), ("weight_hh_l0", "w_hh1"), ("bias_ih_l0", "b_ih1"), ("bias_hh_l0", "b_hh1"),
+                       ("weight_ih_l1", "w_ih2"), ("weight_hh_l1", "w_hh2"), ("bias_ih_l1", "b_ih2"), ("bias_hh_l1", "b_hh2")):
+            getattr(ref, n).copy_(torch.from_numpy(p[key]))
+        h2 = ref(torch.from_numpy(c0)[None])[0][0].numpy()
+    # attention by the exhaustive-search projection, not by the oracle's sparsemax
+    att = np.stack([sum(w * h2[u] for u, w in enumerate(project_by_exhaustive_search(list(h2 @ h2[t])))) for t in range(T)])
+    r = att + c0
+    logp = np.log(probs[0])
+    np.testing.assert_allclose(logp - logp[:, :1], r - r[:, :1], atol=1e-9)

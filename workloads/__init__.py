@@ -8,7 +8,7 @@ only module shared by the CPU oracle's tests and the HIP path's tests / benchmar
 The paper evaluates on SST2 / MRPC / MultiRC sentences fed to Switch Transformers
 (Section 4, "Setup"); none of those are reproduced here.  The arrays below stand in
 for them: only the layer dimensions and a skewed (Zipf) expert popularity, in the
-spirit of the sentence-level activation sparsity of Section 2.3, are kept.
+spirit of the sentence-level activation sparsity of Section 2.4, are kept.
 
 Every array is drawn from its own ``numpy`` PCG64 stream keyed by
 ``SeedSequence([20231018, cfg, layer, stream])`` so any piece can be regenerated
@@ -138,7 +138,7 @@ def gen_batch_ids(wl: Workload, batch: int, T: int) -> np.ndarray:
     so the experts that are popular in one batch are popular in the next, which is what makes a
     slot pool hit across batches - with an independent draw per (batch, layer).  With T around 100
     and Zipf(1.0) over 128 experts a batch activates about 35-40 % of a layer's experts, the
-    sentence-level sparsity Section 2.3 reports for Switch-base-128."""
+    sentence-level sparsity Section 2.4 reports for Switch-base-128."""
     out = np.empty((wl.L, T), dtype=np.int32)
     for layer in range(wl.L):
         g = np.random.Generator(np.random.PCG64(np.random.SeedSequence(
