@@ -16,10 +16,14 @@
  *    slot pool and the workspace are the caller's, and so are the pinned host weight blocks.
  *  - Streams are passed as raw hipStream_t values cast to void* (NULL = the null stream).
  *  - bf16 = bfloat16 (upper half of an IEEE fp32).  All matrices are row-major.
- *  - One expert is ONE contiguous block of sida_expert_bytes() bytes:
+ *  - One expert is ONE contiguous host block of sida_expert_bytes() bytes:
  *        W_in  bf16 [d_ff, d_model]   (row j = weights of hidden unit j), immediately followed by
  *        W_out bf16 [d_model, d_ff].
- *    Slot s of the pool is the byte range [s*expert_bytes, (s+1)*expert_bytes).
+ *    Slot s of the pool is the byte range [s*expert_bytes, (s+1)*expert_bytes).  Inside a slot
+ *    the library keeps the two matrices in the order its matrix-core kernels read them
+ *    (sida_slot_offset): the prefetch re-orders an expert on its way into the slot, so a slot is
+ *    NOT a byte copy of the host block and is only ever filled through sida_expert_prefetch (or
+ *    the forward calls that prefetch).
  *  - Every function returns SIDA_OK (0) or a negative sida_status.  Arguments and state are
  *    checked before anything else: on SIDA_EINVAL, SIDA_ENOSPC, SIDA_ESTATE, SIDA_ENOMEM,
  *    SIDA_EAGAIN and SIDA_ECLOSED nothing has been enqueued and no bookkeeping has changed.
@@ -29,7 +33,8 @@
  *    enqueued show up at the caller's next stream synchronisation, as with any HIP work.
  *  - A context is not thread-safe (the hash-table queue calls excepted); use one per serving thread.  All compute of one context must
  *    be enqueued on one stream, all copies on one (other) stream.
- *  - Limits: 1 <= E <= SIDA_MAX_E; d_model and d_ff multiples of 128; 1 <= W <= S.
+ *  - Limits: 1 <= E <= SIDA_MAX_E; d_model and d_ff multiples of 128, 128 .. 4096; 1 <= W <= S;
+ *    max_T * max(d_model, d_ff) * 2 < 2^31 (rows are addressed with 32-bit byte offsets).
  */
 #ifndef SIDA_MOE_H
 #define SIDA_MOE_H
@@ -129,6 +134,14 @@ int sida_last_hip_error(const sida_ctx *ctx);
 /* 4 * d_model * d_ff: W_in and W_out of one expert in bf16 (two d_model x d_ff matrices, the
  * per-expert parameter count behind Table 2 of Section 2.2). */
 size_t sida_expert_bytes(const sida_ctx *ctx);
+/* Where the slot keeps element [row, col] of an expert's matrix (which = 0: W_in [d_ff, d_model],
+ * 1: W_out [d_model, d_ff]), in bytes from the start of the slot; (size_t)-1 on bad arguments.
+ * A matrix [R, K] is stored in stripes of 32 rows; inside a stripe the 16-byte pieces (8
+ * consecutive K values of one row) are ordered piece-major, row-minor, so that the 32 rows x 16
+ * K values one 32x32x16 matrix-core instruction takes as an operand are 1 KiB of consecutive
+ * memory:  offset = ((row/32) * (K/8) + col/8) * 512 + (row%32) * 16 + (col%8) * 2.
+ * For tests and tools that inspect the pool. */
+size_t sida_slot_offset(const sida_ctx *ctx, int32_t which, int32_t row, int32_t col);
 /* Workspace bytes a layer call with T tokens needs (0 on bad arguments). */
 size_t sida_workspace_bytes(const sida_ctx *ctx, int32_t T);
 int sida_workspace_layout(const sida_ctx *ctx, int32_t T, sida_ws_layout *out);
@@ -153,11 +166,13 @@ int sida_streams_create(int32_t copy_cus, void **compute_stream, void **copy_str
 int sida_streams_destroy(void *compute_stream, void *copy_stream);
 
 /* How sida_expert_prefetch moves an expert into its slot.
- *   SIDA_PREFETCH_COPY_ENGINE  one hipMemcpyAsync per expert (works with pageable host memory too);
+ *   SIDA_PREFETCH_COPY_ENGINE  one hipMemcpyAsync per expert (works with pageable host memory too),
+ *                              then one kernel per wave that re-orders the copied slots in place;
  *   SIDA_PREFETCH_KERNEL       one copy kernel per wave that reads the pinned blocks over the host
- *                              link itself: no per-expert cost (57 GB/s against 45 GB/s measured
- *                              with 9.4 MB experts); needs every bound block in pinned memory,
- *                              SIDA_ESTATE otherwise (bind the weights first);
+ *                              link itself and writes the slot order directly: no per-expert cost
+ *                              (57 GB/s against 45 GB/s measured with 9.4 MB experts); needs every
+ *                              bound block in pinned memory, SIDA_ESTATE otherwise (bind the
+ *                              weights first);
  *   SIDA_PREFETCH_AUTO         the kernel when every bound block is pinned, else the copy engine
  *                              (default). */
 enum { SIDA_PREFETCH_AUTO = 0, SIDA_PREFETCH_COPY_ENGINE = 1, SIDA_PREFETCH_KERNEL = 2 };

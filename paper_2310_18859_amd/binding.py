@@ -70,6 +70,7 @@ def lib():
         "sida_last_hip_error": (C.c_int, [vp]),
         "sida_expert_bytes": (sz, [vp]),
         "sida_workspace_bytes": (sz, [vp, i32]),
+        "sida_slot_offset": (sz, [vp, i32, i32, i32]),
         "sida_workspace_layout": (C.c_int, [vp, i32, C.POINTER(WsLayout)]),
         "sida_bind_pool": (C.c_int, [vp, vp, sz]),
         "sida_bind_host_weights": (C.c_int, [vp, C.POINTER(vp)]),
@@ -201,6 +202,9 @@ class Context:
     # ---- sizes
     def expert_bytes(self) -> int:
         return lib().sida_expert_bytes(self._h)
+
+    def slot_offset(self, which, row, col) -> int:
+        return lib().sida_slot_offset(self._h, which, row, col)
 
     def workspace_bytes(self, T) -> int:
         return lib().sida_workspace_bytes(self._h, T)

@@ -231,6 +231,12 @@ int enqueue_prefetch(sida_ctx *c, const sida_plan *p, int32_t w, hipStream_t cop
         {
             Timed tm(c, SIDA_K_COPY, copy);
             const bool by_kernel = c->prefetch_mode != SIDA_PREFETCH_COPY_ENGINE && !c->host_blocks_dev.empty();
+            // by kernel: the copy writes the slot layout itself; by copy engine: the host block lands
+            // as it is and the slots are re-ordered in place afterwards
+            auto flush = [&](const CopyTable &t) {
+                return by_kernel ? launch_expert_copy(t, c->cfg.d_model, c->cfg.d_ff, copy)
+                                 : launch_slot_relayout(t, c->cfg.d_model, c->cfg.d_ff, copy);
+            };
             CopyTable tbl;
             tbl.n = 0;
             for (int32_t i = 0; i < p->n_active; ++i) {
@@ -238,18 +244,16 @@ int enqueue_prefetch(sida_ctx *c, const sida_plan *p, int32_t w, hipStream_t cop
                 if (p->wave[e] != g || p->hit[e] != 0) continue;
                 const size_t key = (size_t)p->layer * c->cfg.E + e;
                 char *dst = c->pool + (size_t)p->slot[e] * c->expert_bytes;
-                if (!by_kernel) {
+                if (!by_kernel)
                     HIP_TRY(c, hipMemcpyAsync(dst, c->host_blocks[key], c->expert_bytes, hipMemcpyHostToDevice, copy));
-                    continue;
-                }
-                tbl.src[tbl.n] = c->host_blocks_dev[key];
+                tbl.src[tbl.n] = by_kernel ? c->host_blocks_dev[key] : nullptr;
                 tbl.dst[tbl.n] = dst;
                 if (++tbl.n == kCopyBatch) {
-                    HIP_TRY(c, (hipError_t)launch_expert_copy(tbl, c->expert_bytes, copy));
+                    HIP_TRY(c, (hipError_t)flush(tbl));
                     tbl.n = 0;
                 }
             }
-            if (tbl.n) HIP_TRY(c, (hipError_t)launch_expert_copy(tbl, c->expert_bytes, copy));
+            if (tbl.n) HIP_TRY(c, (hipError_t)flush(tbl));
         }
         HIP_TRY(c, hipEventRecord(c->ev_ready[ring], copy));
         c->ready_recorded[ring] = 1;
@@ -291,7 +295,7 @@ int launch_tiles(sida_ctx *c, const LayerSchedule &s, const Ws &ws, hipStream_t 
 }
 
 // x, y != NULL: the fused path - GEMM 1 reads x through perm, GEMM 2 scales by the gate and writes y.
-int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws, hipStream_t st,
+int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws, int32_t T, hipStream_t st,
                     const void *x = nullptr, void *y = nullptr)
 {
     const TileDesc *tiles = ws.tiles + s.tile_begin[w];
@@ -299,12 +303,12 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
         TimedKernel tk(c, SIDA_K_GEMM1);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(x ? x : ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
-                                                x ? ws.perm : nullptr, c->top_k, s.tbl.tile_m));
+                                                x ? T / c->top_k : T, x ? ws.perm : nullptr, T, c->top_k, s.tbl.tile_m));
     }
     {
         TimedKernel tk(c, SIDA_K_GEMM2);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, y ? y : ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
-                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
+                                                s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(), T,
                                                 y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr, s.tbl.tile_m));
     }
     return SIDA_OK;
@@ -390,7 +394,7 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
             const int ring = g % kEventRing;
             if (c->ready_recorded[ring]) HIP_TRY(c, hipStreamWaitEvent(compute, c->ev_ready[ring], 0));
             // with several experts per token a y row is a sum over tiles: only the gather is folded in
-            rc = launch_wave_ffn(c, sched, w, ws, compute, fused ? a.x : nullptr,
+            rc = launch_wave_ffn(c, sched, w, ws, p->T, compute, fused ? a.x : nullptr,
                                  fused && c->top_k == 1 ? a.y : nullptr);
             if (rc) return rc;
             if (g >= kEventRing) HIP_TRY(c, hipEventSynchronize(c->ev_done[ring]));
@@ -416,8 +420,10 @@ int sida_create(const sida_config *cfg, sida_ctx **out)
     *out = nullptr;
     if (cfg->L < 1 || cfg->E < 1 || cfg->E > SIDA_MAX_E || cfg->S < 1 || cfg->S > 32767 || cfg->W < 1 ||
         cfg->W > cfg->S || cfg->W > SIDA_MAX_E || cfg->max_T < 0 || cfg->d_model < 128 || cfg->d_ff < 128 ||
-        cfg->d_model % 128 || cfg->d_ff % 128)
+        cfg->d_model % 128 || cfg->d_ff % 128 || cfg->d_model > kMaxRelayoutK || cfg->d_ff > kMaxRelayoutK)
         return SIDA_EINVAL;
+    // the kernels address activation rows with 32-bit byte offsets
+    if ((int64_t)cfg->max_T * std::max(cfg->d_model, cfg->d_ff) * 2 > INT32_MAX) return SIDA_EINVAL;
     if ((int64_t)cfg->L * cfg->E > INT32_MAX) return SIDA_EINVAL;
     sida_ctx *c = new (std::nothrow) sida_ctx;
     if (!c) return SIDA_ENOMEM;
@@ -472,6 +478,14 @@ const char *sida_strerror(int code)
 int sida_last_hip_error(const sida_ctx *c) { return c ? c->last_hip : 0; }
 
 size_t sida_expert_bytes(const sida_ctx *c) { return c ? c->expert_bytes : 0; }
+
+size_t sida_slot_offset(const sida_ctx *c, int32_t which, int32_t row, int32_t col)
+{
+    if (!c || which < 0 || which > 1 || row < 0 || col < 0) return (size_t)-1;
+    const size_t R = which == 0 ? c->cfg.d_ff : c->cfg.d_model, K = which == 0 ? c->cfg.d_model : c->cfg.d_ff;
+    if ((size_t)row >= R || (size_t)col >= K) return (size_t)-1;
+    return (which == 0 ? 0 : R * K * 2) + slot_piece_offset(row, col / 8, K) + (size_t)(col % 8) * 2;
+}
 
 size_t sida_workspace_bytes(const sida_ctx *c, int32_t T)
 {
@@ -819,7 +833,7 @@ int sida_grouped_ffn(sida_ctx *c, const sida_plan *plan, int32_t wave, void *wor
     const Ws ws = carve(c->cfg, plan->T, workspace_dev);
     rc = launch_tiles(c, sched, ws, static_cast<hipStream_t>(stream));
     if (rc) return rc;
-    return launch_wave_ffn(c, sched, wave, ws, static_cast<hipStream_t>(stream));
+    return launch_wave_ffn(c, sched, wave, ws, plan->T, static_cast<hipStream_t>(stream));
 }
 
 int sida_combine(sida_ctx *c, const float *alpha_dev, int32_t T, void *y_dev, void *workspace_dev,

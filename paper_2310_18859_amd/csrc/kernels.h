@@ -49,14 +49,30 @@ int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void
 // With a row map (perm, and for GEMM 2 gate_perm) the gather / combine passes are folded in:
 // GEMM 1 then reads row r from x[perm[r] / k] (x_perm = x in token order, k rows per token), GEMM 2 writes
 // bf16(gate_perm[r] * result row r) to y[perm[r]] (y_perm = y in token order).
+// a_rows: rows of the token operand (x_perm / h, or x when gathering), map_len: entries of perm.
+// The experts are read from their pool slots in the slot layout below.
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
-                     int32_t k = 1, int32_t tile_m = 128);
+                     hipStream_t st, const LaunchEvents *ev, int32_t a_rows, const int32_t *perm = nullptr,
+                     int32_t map_len = 0, int32_t k = 1, int32_t tile_m = 128);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
-                     hipStream_t st, const LaunchEvents *ev = nullptr, const int32_t *perm = nullptr,
+                     hipStream_t st, const LaunchEvents *ev, int32_t a_rows, const int32_t *perm = nullptr,
                      const float *gate_perm = nullptr, int32_t tile_m = 128);
+
+// Slot layout.  The host block of an expert is W_in [F, d] then W_out [d, F], row-major (the ABI);
+// a pool slot holds the same two matrices, each in MFMA-fragment order: a matrix [R, K] is cut
+// into stripes of 32 rows, and the 16-byte piece p (K values 8p .. 8p+7) of row r is stored at
+//     ((r / 32) * (K / 8) + p) * 512 + (r % 32) * 16
+// bytes from the matrix's start - a 32 x (K/8) matrix of pieces per stripe, transposed.  The 32
+// rows x 16 K values a 32x32x16 MFMA takes as one operand (pieces 2j and 2j+1 of a stripe) are
+// then 1 KiB of consecutive memory with lane l's 16 bytes at offset 16*l.  A stripe occupies the
+// same bytes in both layouts, so a slot can be re-ordered in place, stripe by stripe.
+inline size_t slot_piece_offset(size_t r, size_t p, size_t K) { return ((r / 32) * (K / 8) + p) * 512 + (r % 32) * 16; }
+// Re-orders, in place, the n slots listed in tbl.dst from host-block order to slot order (after a
+// plain copy of the host block into the slot).  d, F <= kMaxRelayoutK (a stripe is held in the
+// registers of one workgroup).
+constexpr int kMaxRelayoutK = 4096;
 // A stream is about to be destroyed: drop what is cached about it (its handle may be reused).
 void forget_stream(hipStream_t st);
 // Expands tbl into token tiles: entry i gets ceil(count_i / tbl.tile_m) consecutive descriptors,
@@ -75,7 +91,9 @@ struct CopyTable {
     const void *src[kCopyBatch];
     void *dst[kCopyBatch];
 };
-int launch_expert_copy(const CopyTable &tbl, size_t expert_bytes, hipStream_t st);
+// Copies the listed experts host -> slot, re-ordering them into the slot layout on the way.
+int launch_expert_copy(const CopyTable &tbl, int32_t d, int32_t F, hipStream_t st);
+int launch_slot_relayout(const CopyTable &tbl, int32_t d, int32_t F, hipStream_t st);
 
 // The hash function (hash_fn.hip).  C is 64 or 128; ws holds 8*C floats per token.
 struct HashShape {

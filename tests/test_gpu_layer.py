@@ -12,6 +12,17 @@ from workloads import WORKLOADS, Workload, f32_to_bf16_bits
 pytestmark = pytest.mark.gpu
 
 
+def slot_order(block, d, F):
+    """An expert's host block (W_in [F, d] then W_out [d, F], row-major) in the order a pool slot
+    keeps it: per matrix [R, K], stripes of 32 rows; inside a stripe the 8-element pieces are
+    stored piece-major, row-minor - written here with reshapes only."""
+    out = []
+    for m, (R, K) in ((block[:F * d], (F, d)), (block[F * d:], (d, F))):
+        pieces = m.reshape(R // 32, 32, K // 8, 8)            # [stripe, row in stripe, piece, element]
+        out.append(pieces.transpose(0, 2, 1, 3).reshape(-1))  # [stripe, piece, row in stripe, element]
+    return np.concatenate(out)
+
+
 def run_and_check(wl, reps=1, T_of=None, check_plan=True, fused=False):
     """Runs all layers `reps` times through sida_run_layers and checks every layer's y, its sort
     outputs and its plan against the oracle."""
@@ -201,12 +212,22 @@ def test_prefetch_by_copy_engine_and_by_kernel(mode):
             x_bits, ids, alpha = ins[l]
             y = bf16_tensor_to_f32(dev[l][3])
             worst = max(worst, assert_close(y, oracle_layer(wl, r, l, x_bits, ids, alpha), f"{mode} rep {rep} layer {l}"))
-    # the pool holds exactly what the plan says, byte for byte
+    # the pool holds exactly what the plan says: every slot is its expert's host block in the
+    # documented slot order (stripes of 32 rows, 16-byte pieces piece-major inside a stripe)
     keys, _, _ = r.ctx.pool_state()
     hw = r.host_weights.numpy()
     pool = r.pool.view(torch.uint16).reshape(wl.S, -1).cpu().numpy()
     for s, key in enumerate(keys):
         if key >= 0:
-            assert np.array_equal(pool[s], hw[key]), f"slot {s}"
+            assert np.array_equal(pool[s], slot_order(hw[key], wl.d_model, wl.d_ff)), f"slot {s}"
+    # ... and sida_slot_offset names the same places
+    rng = np.random.default_rng(3)
+    s0 = next(s for s, k in enumerate(keys) if k >= 0)
+    for which, (R, K) in enumerate(((wl.d_ff, wl.d_model), (wl.d_model, wl.d_ff))):
+        for _ in range(50):
+            row, col = int(rng.integers(R)), int(rng.integers(K))
+            off = r.ctx.slot_offset(which, row, col)
+            assert off % 2 == 0 and pool[s0][off // 2] == hw[keys[s0]][which * wl.d_model * wl.d_ff + row * K + col]
+    assert r.ctx.slot_offset(0, wl.d_ff, 0) == 2 ** 64 - 1 and r.ctx.slot_offset(2, 0, 0) == 2 ** 64 - 1
     r.close()
     say(f"  max rel err {worst:.3e}")
