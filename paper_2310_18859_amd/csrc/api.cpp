@@ -176,6 +176,9 @@ struct LayerSchedule {
 // 6 % slower at 128 tokens per expert.)
 int32_t choose_tile_m(const sida_plan *p)
 {
+    // A layer that is cut into waves launches a few experts at a time: small launches, hidden
+    // behind the copies; 64-row tiles give them more (and deeper-fetching) tiles.
+    if (p->n_waves > 1) return kGemmTileSmall;
     int64_t t64 = 0, t128 = 0;
     for (int32_t i = 0; i < p->n_active; ++i) {
         const int32_t n = p->counts[p->order[i]];

@@ -90,7 +90,6 @@ __device__ __forceinline__ bf16x8 load_frag(__amdgpu_buffer_rsrc_t r, int voffse
 enum { kPlain = 0, kGather = 1, kScatter = 2 };
 
 constexpr int kWaves = 4;        // wavefronts per workgroup
-constexpr int kNB = 2;           // K-steps both operands are fetched ahead; K/64 is a multiple of it
 
 struct GemmArgs {
     const __bf16 *A;             // token rows [a_rows, K]
@@ -108,15 +107,16 @@ struct GemmArgs {
 
 // Persistent workgroups: two per compute unit, each walks its tiles t = b, b+G, ...
 //
-// (tile, K-step) is ONE stream of steps: the loads run kNB steps ahead of the MFMAs, also across
-// tile boundaries (the last kNB steps of a tile already fetch the next one; a workgroup's last tile
+// (tile, K-step) is ONE stream of steps: the loads run NB steps ahead of the MFMAs (K/64 is a
+// multiple of NB), also across
+// tile boundaries (the last NB steps of a tile already fetch the next one; a workgroup's last tile
 // fetches its own first steps once more, unused, so that the loop has no data-dependent branch).
 // Per step a wavefront executes: one s_waitcnt, one s_barrier, its share of the token loads, and
 // per 16 K values BM/32 LDS fragment reads, NS*BM/32 MFMAs and NS weight-fragment loads.
-template <int BM, int NS, bool RELU, int FUSE>
+template <int BM, int NS, int NB, bool RELU, int FUSE>
 __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs g)
 {
-    constexpr int NWV = kWaves, NB = kNB;
+    constexpr int NWV = kWaves;
     constexpr int BN = NWV * NS * 32;
     constexpr int TS = NB + 1;                                  // token ring stages
     constexpr int kStageBytes = BM * 128;
@@ -368,25 +368,18 @@ int persistent_grid(hipStream_t st)
     return cus;
 }
 
-// One GEMM of the pair as one launch: BM token rows per tile, 4*NS*32 weight rows.
-template <int BM, int NS, bool RELU, int FUSE>
+// One GEMM of the pair as one launch: BM token rows per tile, 4*NS*32 weight rows, NB K-steps ahead.
+template <int BM, int NS, int NB, bool RELU, int FUSE>
 int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
 {
-    constexpr int kLdsBytes = (kNB + 1) * BM * 128 + kWaves * 32 * (NS * 64 + 16) +
+    constexpr int kLdsBytes = (NB + 1) * BM * 128 + kWaves * 32 * (NS * 64 + 16) +
                               kWaves * (FUSE == kPlain ? 0 : (FUSE == kGather ? 256 : 2 * BM * 4));
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, NS, RELU, FUSE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, NS, NB, RELU, FUSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
-    }
-    if (a.m_tiles <= 0) {                                    // nothing to launch: keep the events usable
-        if (ev) {
-            (void)hipEventRecord(ev->start, st);
-            (void)hipEventRecord(ev->stop, st);
-        }
-        return 0;
     }
     GemmArgs g = a;
     const int n_tiles_n = a.N / (kWaves * NS * 32);
@@ -394,21 +387,45 @@ int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
     const int total = a.m_tiles * n_tiles_n;
     const int cap = 2 * persistent_grid(st);                 // two workgroups per compute unit
     const int grid = total < cap ? (total + 7) / 8 * 8 : cap;   // multiple of 8 XCDs
-    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, NS, RELU, FUSE>), dim3(grid), dim3(kWaves * 64), kLdsBytes, st,
+    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, NS, NB, RELU, FUSE>), dim3(grid), dim3(kWaves * 64), kLdsBytes, st,
                           ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, g);
     return (int)hipGetLastError();
 }
 
-// Tile shape of a launch: BM = 64 or 128 token rows as the layer's descriptors say; 256 weight rows
-// per tile (two stripes per wavefront, one LDS read per two MFMAs) wherever the matrix has a
-// multiple of 256 rows - every Switch shape has - else 128.
+// Tile shape of a launch.  BM = 64 or 128 token rows as the layer's descriptors say.  Weight rows per
+// tile: 256 (two stripes per wavefront, one LDS fragment read per two MFMAs) when the matrix has a
+// multiple of 256 rows - every Switch shape has - unless 128-row tiles, twice as many at a little
+// more than half the time each (measured: 0.55), need fewer rounds over the persistent grid's
+// workgroup slots: tiles are dealt to the workgroups in turn, so a launch takes as long as its
+// workgroup with the most tiles.  A launch that leaves
+// workgroup slots idle streams every tile's weights through few registers per compute unit, so
+// narrow 64-row tiles also fetch four K-steps ahead instead of two where the K loop allows it (with
+// 128-row tiles a five-stage token ring would not leave room for two workgroups per compute unit,
+// and the loads of a wavefront complete in order, so the ring has to be as deep as the weights).
+template <int BM, bool RELU, int FUSE>
+int launch_width(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
+{
+    const int64_t slots = 2 * (int64_t)persistent_grid(st);
+    const int64_t t_wide = (int64_t)a.m_tiles * (a.N / 256);
+    const bool wide = a.N % 256 == 0 && (t_wide + slots - 1) / slots * 20 <= (2 * t_wide + slots - 1) / slots * 11;
+    if (wide) return launch_as<BM, 2, 2, RELU, FUSE>(a, st, ev);
+    if constexpr (BM == kGemmTileSmall)
+        if (a.K % 256 == 0) return launch_as<BM, 1, 4, RELU, FUSE>(a, st, ev);
+    return launch_as<BM, 1, 2, RELU, FUSE>(a, st, ev);
+}
+
 template <bool RELU, int FUSE>
 int launch_shape(const GemmArgs &a, int tile_m, hipStream_t st, const LaunchEvents *ev)
 {
-    const bool wide = a.N % 256 == 0;
-    if (tile_m == kGemmTileSmall)
-        return wide ? launch_as<kGemmTileSmall, 2, RELU, FUSE>(a, st, ev) : launch_as<kGemmTileSmall, 1, RELU, FUSE>(a, st, ev);
-    return wide ? launch_as<kGemmTileM, 2, RELU, FUSE>(a, st, ev) : launch_as<kGemmTileM, 1, RELU, FUSE>(a, st, ev);
+    if (a.m_tiles <= 0) {                                    // nothing to launch: keep the events usable
+        if (ev) {
+            (void)hipEventRecord(ev->start, st);
+            (void)hipEventRecord(ev->stop, st);
+        }
+        return 0;
+    }
+    if (tile_m == kGemmTileSmall) return launch_width<kGemmTileSmall, RELU, FUSE>(a, st, ev);
+    return launch_width<kGemmTileM, RELU, FUSE>(a, st, ev);
 }
 
 }  // namespace
