@@ -280,7 +280,8 @@ int sida_set_top_k(sida_ctx *ctx, int32_t k);
  * about two thirds of the dispatch/combine HBM traffic less per layer.  With more than one expert
  * per token only the gather is folded in (a y row is then a sum over several tiles).  Affects
  * sida_moe_layer_forward / sida_run_layers only; the single-stage calls keep the separate passes.
- * Off by default.  May be switched between layer calls. */
+ * On by default; switching it off brings the separate gather and combine passes (and the x_perm /
+ * y_perm intermediates in the workspace) back.  May be switched between layer calls. */
 int sida_set_fusion(sida_ctx *ctx, int32_t on);
 
 /* Convenience: forwards n consecutive planned layers, keeping the copy stream one wave ahead of

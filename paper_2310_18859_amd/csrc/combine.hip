@@ -13,34 +13,38 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
-// One wavefront per token row; 16-byte accesses (8 bf16 values).
+// 16-byte accesses (8 bf16 values).  The pieces of kCombineRows consecutive token rows are dealt
+// to the 256 threads of a workgroup as one flat range, so that no lane idles whatever the row
+// length (96 pieces at d = 768).
+constexpr int kCombineRows = 16;
 __global__ __launch_bounds__(256) void combine_rows(const bf16x8 *__restrict__ y_perm,
                                                     const int32_t *__restrict__ inv,
                                                     const float *__restrict__ alpha, int n_tokens,
                                                     int vec_per_row, bf16x8 *__restrict__ y, int k)
 {
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= n_tokens) return;
-    const int lane = threadIdx.x & 63;
-    bf16x8 *dst = y + (size_t)t * vec_per_row;
-    for (int i = lane; i < vec_per_row; i += 64) {
+    const int t0 = blockIdx.x * kCombineRows;
+    const int n = min(kCombineRows, n_tokens - t0) * vec_per_row;   // pieces of this workgroup
+    bf16x8 *dst = y + (size_t)t0 * vec_per_row;               // its token rows are one contiguous range
+    for (int p = threadIdx.x; p < n; p += 256) {
+        const int r = p / vec_per_row, i = p - r * vec_per_row;
+        const size_t t = (size_t)(t0 + r) * k;
         float acc[8];
         {
-            const float a = alpha[(size_t)t * k];
-            const bf16x8 v = y_perm[(size_t)inv[(size_t)t * k] * vec_per_row + i];
+            const float a = alpha[t];
+            const bf16x8 v = y_perm[(size_t)inv[t] * vec_per_row + i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] = a * (float)v[j];
         }
         for (int s = 1; s < k; ++s) {
-            const float a = alpha[(size_t)t * k + s];
-            const bf16x8 v = y_perm[(size_t)inv[(size_t)t * k + s] * vec_per_row + i];
+            const float a = alpha[t + s];
+            const bf16x8 v = y_perm[(size_t)inv[t + s] * vec_per_row + i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += a * (float)v[j];
         }
         bf16x8 o;
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[j] = (__bf16)acc[j];
-        dst[i] = o;
+        dst[p] = o;
     }
 }
 
@@ -50,7 +54,7 @@ int launch_combine(const void *y_perm, const int32_t *inv, const float *alpha, i
                    void *y, hipStream_t st, const LaunchEvents *ev, int32_t k)
 {
     const int n_tokens = T / k;
-    hipExtLaunchKernelGGL(combine_rows, dim3((n_tokens + 3) / 4), dim3(256), 0, st, ev ? ev->start : nullptr,
+    hipExtLaunchKernelGGL(combine_rows, dim3((n_tokens + kCombineRows - 1) / kCombineRows), dim3(256), 0, st, ev ? ev->start : nullptr,
                           ev ? ev->stop : nullptr, 0, (const bf16x8 *)y_perm, inv, alpha, n_tokens, d / 8,
                           (bf16x8 *)y, k);
     return (int)hipGetLastError();

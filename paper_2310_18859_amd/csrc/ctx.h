@@ -66,7 +66,7 @@ struct sida_ctx {
     std::vector<uint8_t> ready_recorded;  // ring: wave g recorded a ready event (it had misses)
     bool events_made = false;
 
-    bool fused = false;                // gather / combine folded into the grouped GEMMs
+    bool fused = true;                 // gather / combine folded into the grouped GEMMs (the default)
     int32_t top_k = 1;                 // experts per token (rows of a layer call = tokens * top_k)
 
     // kernel timing

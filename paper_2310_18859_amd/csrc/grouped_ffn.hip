@@ -395,7 +395,7 @@ int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
 // Tile shape of a launch.  BM = 64 or 128 token rows as the layer's descriptors say.  Weight rows per
 // tile: 256 (two stripes per wavefront, one LDS fragment read per two MFMAs) when the matrix has a
 // multiple of 256 rows - every Switch shape has - unless 128-row tiles, twice as many at a little
-// more than half the time each (measured: 0.55), need fewer rounds over the persistent grid's
+// more than half the time each (fitted: 5/8), need fewer rounds over the persistent grid's
 // workgroup slots: tiles are dealt to the workgroups in turn, so a launch takes as long as its
 // workgroup with the most tiles.  A launch that leaves
 // workgroup slots idle streams every tile's weights through few registers per compute unit, so
@@ -407,7 +407,7 @@ int launch_width(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
 {
     const int64_t slots = 2 * (int64_t)persistent_grid(st);
     const int64_t t_wide = (int64_t)a.m_tiles * (a.N / 256);
-    const bool wide = a.N % 256 == 0 && (t_wide + slots - 1) / slots * 20 <= (2 * t_wide + slots - 1) / slots * 11;
+    const bool wide = a.N % 256 == 0 && (t_wide + slots - 1) / slots * 8 <= (2 * t_wide + slots - 1) / slots * 5;
     if (wide) return launch_as<BM, 2, 2, RELU, FUSE>(a, st, ev);
     if constexpr (BM == kGemmTileSmall)
         if (a.K % 256 == 0) return launch_as<BM, 1, 4, RELU, FUSE>(a, st, ev);

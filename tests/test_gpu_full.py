@@ -25,6 +25,9 @@ def check_workload(wl, layers_checked, whole_layer=0):
     ins = [layer_inputs(wl, l) for l in range(wl.L)]
     worst = 0.0
     for rep in range(2):                                  # second pass: the pool starts in its steady state
+        # first pass with separate gather / combine passes (x_perm is then checked below), second
+        # pass as bench.py runs it: the library's default, both folded into the GEMMs
+        r.ctx.set_fusion(rep == 1)
         plans = r.plan_all([i[1] for i in ins])
         dev = [r.to_device(*i) for i in ins]
         r.run(plans, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], [d[3] for d in dev])
