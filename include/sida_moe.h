@@ -248,7 +248,8 @@ int sida_expert_prefetch(sida_ctx *ctx, const sida_plan *plan, int32_t wave, voi
  * (W_in GEMM, ReLU, W_out GEMM on bf16 MFMA, fp32 accumulate, experts addressed through the
  * plan's slot table); gate-weighted scatter back to token order.
  *   x_dev     bf16 [T, d_model]    device, read
- *   ids_dev   int32 [T]            device, read; must equal the ids the plan was made from
+ *   ids_dev   int32 [T]            device, read; must equal the ids the plan was made from (not
+ *                                  checked unless SIDA_DEBUG_CHECK_IDS is on)
  *   alpha_dev fp32 [T]             device, read; the per-token scaling factor (gate value)
  *   y_dev     bf16 [T, d_model]    device, written
  *   workspace_dev                  device, >= sida_workspace_bytes(T), 256-byte aligned, scratch
@@ -283,6 +284,28 @@ int sida_set_top_k(sida_ctx *ctx, int32_t k);
  * On by default; switching it off brings the separate gather and combine passes (and the x_perm /
  * y_perm intermediates in the workspace) back.  May be switched between layer calls. */
 int sida_set_fusion(sida_ctx *ctx, int32_t on);
+
+/* Debug switches, off by default (any combination; 0 switches all off and clears a latched mismatch).
+ *   SIDA_DEBUG_CHECK_IDS     sida_moe_layer_forward trusts that ids_dev holds the ids the plan was
+ *                            made from (a mismatch would compute with slots and tiles that do not
+ *                            belong to the rows).  With this switch every layer call also compares
+ *                            the per-expert token counts its sort found on the device with the
+ *                            plan's; a difference is latched, and from the moment the host sees it
+ *                            every sida_expert_prefetch / forward call returns SIDA_ESTATE until
+ *                            sida_pool_reset or sida_set_debug.  The check runs on the stream, so
+ *                            it is seen at the latest by the first call after the stream was
+ *                            synchronised; sida_debug_mismatch_layer names the layer (-1: none).
+ *                            Costs one small launch per layer; the first use allocates one
+ *                            pinned host word (not device memory).
+ *   SIDA_DEBUG_POISON_SLOTS  a slot that is about to be reloaded is first filled with NaNs (on the
+ *                            copy stream, once the last wave that read its old contents is done),
+ *                            so that a grouped FFN that ran before its wave's copies were complete
+ *                            - a broken wave / event order - shows up as NaN in y instead of as
+ *                            stale but plausible numbers (the slot-reuse race between the copy
+ *                            and the compute stream is the one race of this design). */
+enum { SIDA_DEBUG_CHECK_IDS = 1, SIDA_DEBUG_POISON_SLOTS = 2 };
+int sida_set_debug(sida_ctx *ctx, int32_t flags);
+int sida_debug_mismatch_layer(const sida_ctx *ctx);
 
 /* Convenience: forwards n consecutive planned layers, keeping the copy stream one wave ahead of
  * the compute across layer boundaries too (the first wave of layer i+1 is copied while the last

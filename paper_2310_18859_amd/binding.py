@@ -8,6 +8,7 @@ SIDA_MAX_E = 256
 POLICY_FIFO, POLICY_LRU, POLICY_BELADY = 0, 1, 2
 POLICIES = {"fifo": POLICY_FIFO, "lru": POLICY_LRU, "belady": POLICY_BELADY}
 EAGAIN, ECLOSED = -6, -7
+DEBUG_CHECK_IDS, DEBUG_POISON_SLOTS = 1, 2
 K_NAMES = ("sort", "gather", "gemm1", "gemm2", "combine", "copy")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -80,6 +81,8 @@ def lib():
         "sida_moe_plan_lookahead": (C.c_int, [vp, i32, vp, i32, vp, C.c_int64, C.POINTER(SidaPlan)]),
         "sida_set_policy": (C.c_int, [vp, i32, i32]),
         "sida_set_fusion": (C.c_int, [vp, i32]),
+        "sida_set_debug": (C.c_int, [vp, i32]),
+        "sida_debug_mismatch_layer": (C.c_int, [vp]),
         "sida_set_prefetch_mode": (C.c_int, [vp, i32]),
         "sida_tile_order": (C.c_int, [i32, i32, i32, vp, vp]),
         "sida_hash_param_count": (sz, [C.POINTER(SidaHashConfig)]),
@@ -264,6 +267,13 @@ class Context:
 
     def set_fusion(self, on: bool):
         self._ck(lib().sida_set_fusion(self._h, 1 if on else 0), "sida_set_fusion")
+
+    def set_debug(self, flags: int):
+        """flags: DEBUG_CHECK_IDS | DEBUG_POISON_SLOTS."""
+        self._ck(lib().sida_set_debug(self._h, flags), "sida_set_debug")
+
+    def debug_mismatch_layer(self) -> int:
+        return lib().sida_debug_mismatch_layer(self._h)
 
     def set_policy(self, policy, lookahead_batches=0):
         self._ck(lib().sida_set_policy(self._h, POLICIES.get(policy, policy), lookahead_batches), "sida_set_policy")

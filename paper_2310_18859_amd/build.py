@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsida_moe.so")
-SOURCES = ["api.cpp", "plan.cpp", "sort_gather.hip", "grouped_ffn.hip", "combine.hip", "prefetch.hip", "hash_fn.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "sort_gather.hip", "grouped_ffn.hip", "combine.hip", "prefetch.hip", "hash_fn.hip", "debug.hip"]
 HEADERS = ["ctx.h", "kernels.h", "tile_order.h"]
 
 

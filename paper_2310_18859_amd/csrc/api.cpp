@@ -105,6 +105,9 @@ int check_plan(const sida_ctx *c, const sida_plan *p)
     return SIDA_OK;
 }
 
+// A layer whose device-side token counts differed from its plan's was seen (SIDA_DEBUG_CHECK_IDS).
+bool ids_mismatch_latched(const sida_ctx *c) { return c->debug_flag && *static_cast<volatile int32_t *>(c->debug_flag) != 0; }
+
 int check_ws(const sida_ctx *c, int32_t T, const void *ws, size_t bytes)
 {
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SIDA_EINVAL;
@@ -240,6 +243,21 @@ int enqueue_prefetch(sida_ctx *c, const sida_plan *p, int32_t w, hipStream_t cop
                 return by_kernel ? launch_expert_copy(t, c->cfg.d_model, c->cfg.d_ff, copy)
                                  : launch_slot_relayout(t, c->cfg.d_model, c->cfg.d_ff, copy);
             };
+            if (c->debug & SIDA_DEBUG_POISON_SLOTS) {           // after the wait above: the slots' last readers are done
+                CopyTable pt;
+                pt.n = 0;
+                for (int32_t i = 0; i < p->n_active; ++i) {
+                    const int32_t e = p->order[i];
+                    if (p->wave[e] != g || p->hit[e] != 0) continue;
+                    pt.src[pt.n] = nullptr;
+                    pt.dst[pt.n] = c->pool + (size_t)p->slot[e] * c->expert_bytes;
+                    if (++pt.n == kCopyBatch) {
+                        HIP_TRY(c, (hipError_t)launch_poison_slots(pt, c->expert_bytes, copy));
+                        pt.n = 0;
+                    }
+                }
+                HIP_TRY(c, (hipError_t)launch_poison_slots(pt, c->expert_bytes, copy));
+            }
             CopyTable tbl;
             tbl.n = 0;
             for (int32_t i = 0; i < p->n_active; ++i) {
@@ -340,6 +358,7 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
                    hipStream_t compute, hipStream_t copy)
 {
     if (!c->pool || c->host_blocks.empty()) return SIDA_ESTATE;
+    if (ids_mismatch_latched(c)) return SIDA_ESTATE;
     int32_t expect = c->forwarded_upto;
     for (int32_t i = 0; i < n; ++i) {
         int rc = check_layer_args(c, layers[i]);
@@ -384,6 +403,11 @@ int forward_layers(sida_ctx *c, int32_t n, const LayerArgs *layers, void *ws_dev
         rc = launch_dispatch(c, a.x, a.ids, p->T, ws, &sched.tbl, compute,      // also expands sched.tbl into tiles
                              fused ? a.alpha : nullptr);
         if (rc) return rc;
+        if (c->debug & SIDA_DEBUG_CHECK_IDS) {                 // the sort's counts against the plan's
+            CountTable want;
+            std::memcpy(want.n, p->counts, sizeof want.n);
+            HIP_TRY(c, (hipError_t)launch_check_counts(ws.counts, want, c->cfg.E, p->layer, c->debug_flag_dev, compute));
+        }
         for (int32_t w = 0; w < p->n_waves; ++w) {
             const int32_t g = p->first_wave + w;
             rc = try_prefetch(li, w);
@@ -460,6 +484,7 @@ void sida_destroy(sida_ctx *c)
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
     }
+    if (c->debug_flag) (void)hipHostFree(c->debug_flag);
     delete c;
 }
 
@@ -609,6 +634,7 @@ int sida_pool_reset(sida_ctx *c)
     c->prefetched_upto = 0;
     c->forwarded_upto = 0;
     ++c->epoch;
+    if (c->debug_flag) *c->debug_flag = 0;
     return SIDA_OK;
 }
 
@@ -659,6 +685,31 @@ int sida_set_fusion(sida_ctx *c, int32_t on)
     if (!c) return SIDA_EINVAL;
     c->fused = on != 0;
     return SIDA_OK;
+}
+
+int sida_set_debug(sida_ctx *c, int32_t flags)
+{
+    if (!c || (flags & ~(SIDA_DEBUG_CHECK_IDS | SIDA_DEBUG_POISON_SLOTS))) return SIDA_EINVAL;
+    if ((flags & SIDA_DEBUG_CHECK_IDS) && !c->debug_flag) {    // one pinned word the check kernel can write
+        void *p = nullptr, *d = nullptr;
+        HIP_TRY(c, hipHostMalloc(&p, 64, hipHostMallocMapped));
+        if (hipHostGetDevicePointer(&d, p, 0) != hipSuccess) {
+            (void)hipHostFree(p);
+            c->last_hip = (int)hipGetLastError();
+            return SIDA_EHIP;
+        }
+        c->debug_flag = static_cast<int32_t *>(p);
+        c->debug_flag_dev = static_cast<int32_t *>(d);
+    }
+    if (c->debug_flag) *c->debug_flag = 0;
+    c->debug = flags;
+    return SIDA_OK;
+}
+
+int sida_debug_mismatch_layer(const sida_ctx *c)
+{
+    if (!c) return SIDA_EINVAL;
+    return c->debug_flag ? *static_cast<volatile int32_t *>(c->debug_flag) - 1 : -1;
 }
 
 int sida_set_policy(sida_ctx *c, int32_t policy, int32_t lookahead_batches)
@@ -774,6 +825,7 @@ int sida_expert_prefetch(sida_ctx *c, const sida_plan *plan, int32_t wave, void 
     if (rc) return rc;
     if (wave < 0 || wave >= plan->n_waves) return SIDA_EINVAL;
     if (!c->pool || c->host_blocks.empty()) return SIDA_ESTATE;
+    if (ids_mismatch_latched(c)) return SIDA_ESTATE;
     if (plan->first_wave + wave < c->prefetched_upto) return SIDA_OK;
     rc = prefetch_allowed(c, plan, wave);
     if (rc) return rc;

@@ -82,6 +82,11 @@ struct sida_ctx {
     std::deque<sida::QueuedTable> queue;
     bool q_closed = false;
 
+    // debug switches (sida_set_debug)
+    int32_t debug = 0;
+    int32_t *debug_flag = nullptr;     // pinned host word the check kernel latches a mismatch into
+    int32_t *debug_flag_dev = nullptr; // its device-visible address
+
     int last_hip = 0;
 };
 

@@ -95,6 +95,15 @@ struct CopyTable {
 int launch_expert_copy(const CopyTable &tbl, int32_t d, int32_t F, hipStream_t st);
 int launch_slot_relayout(const CopyTable &tbl, int32_t d, int32_t F, hipStream_t st);
 
+// Debug helpers (debug.hip).  check: latches layer + 1 into *flag_dev (device-visible host memory)
+// when a device-side count differs from the plan's; poison: fills the listed slots with bf16 NaNs.
+struct CountTable {
+    int32_t n[256];
+};
+int launch_check_counts(const int32_t *counts, const CountTable &want, int32_t E, int32_t layer, int32_t *flag_dev,
+                        hipStream_t st);
+int launch_poison_slots(const CopyTable &tbl, size_t expert_bytes, hipStream_t st);
+
 // The hash function (hash_fn.hip).  C is 64 or 128; ws holds 8*C floats per token.
 struct HashShape {
     int32_t d_model, C, L, E, top_k;
