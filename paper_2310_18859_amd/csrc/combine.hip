@@ -13,31 +13,38 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
-// 16-byte accesses (8 bf16 values).  The pieces of kCombineRows consecutive token rows are dealt
-// to the 256 threads of a workgroup as one flat range, so that no lane idles whatever the row
-// length (96 pieces at d = 768).
-constexpr int kCombineRows = 16;
+// 16-byte accesses (8 bf16 values).  A workgroup takes kCombineRows consecutive token rows: their
+// source rows and gate values go to LDS first, then the rows' pieces are dealt to the 256 threads
+// as one flat range, so that no lane idles whatever the row length (96 pieces at d = 768).
+constexpr int kCombineRows = 8;
 __global__ __launch_bounds__(256) void combine_rows(const bf16x8 *__restrict__ y_perm,
                                                     const int32_t *__restrict__ inv,
                                                     const float *__restrict__ alpha, int n_tokens,
                                                     int vec_per_row, bf16x8 *__restrict__ y, int k)
 {
+    __shared__ int src_row[kCombineRows * 8];                 // k <= 8 entries per token
+    __shared__ float gate[kCombineRows * 8];
     const int t0 = blockIdx.x * kCombineRows;
-    const int n = min(kCombineRows, n_tokens - t0) * vec_per_row;   // pieces of this workgroup
+    const int rows = min(kCombineRows, n_tokens - t0);
+    if ((int)threadIdx.x < rows * k) {
+        src_row[threadIdx.x] = inv[(size_t)t0 * k + threadIdx.x];
+        gate[threadIdx.x] = alpha[(size_t)t0 * k + threadIdx.x];
+    }
+    __syncthreads();
+    const int n = rows * vec_per_row;                         // pieces of this workgroup
     bf16x8 *dst = y + (size_t)t0 * vec_per_row;               // its token rows are one contiguous range
     for (int p = threadIdx.x; p < n; p += 256) {
         const int r = p / vec_per_row, i = p - r * vec_per_row;
-        const size_t t = (size_t)(t0 + r) * k;
         float acc[8];
         {
-            const float a = alpha[t];
-            const bf16x8 v = y_perm[(size_t)inv[t] * vec_per_row + i];
+            const float a = gate[r * k];
+            const bf16x8 v = y_perm[(size_t)src_row[r * k] * vec_per_row + i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] = a * (float)v[j];
         }
         for (int s = 1; s < k; ++s) {
-            const float a = alpha[t + s];
-            const bf16x8 v = y_perm[(size_t)inv[t + s] * vec_per_row + i];
+            const float a = gate[r * k + s];
+            const bf16x8 v = y_perm[(size_t)src_row[r * k + s] * vec_per_row + i];
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += a * (float)v[j];
         }

@@ -46,8 +46,10 @@ __global__ __launch_bounds__(256) void copy_experts(const CopyTable tbl, size_t 
         // all loads first, then the stores.  Plain stores: a wave's experts (150 MB at the bench
         // workload) stay in the 256 MB Infinity Cache until the wave's GEMMs read them
 #pragma unroll
-        for (int i = 0; i < kInFlight; ++i)
-            if (base + (size_t)i * 256 < pieces) v[i] = src[base + (size_t)i * 256];
+        for (int i = 0; i < kInFlight; ++i) {                 // unconditional loads (past the end: the last piece again)
+            const size_t j = base + (size_t)i * 256;
+            v[i] = src[j < pieces ? j : pieces - 1];
+        }
 #pragma unroll
         for (int i = 0; i < kInFlight; ++i)
             if (base + (size_t)i * 256 < pieces) dst[slot_piece(base + (size_t)i * 256, pieces_in, kpr_in, kpr_out)] = v[i];
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(kRelayoutThreads) void relayout_slots(const CopyTab
 #pragma unroll
     for (int i = 0; i < kRelayoutPieces; ++i) {
         const int j = i * kRelayoutThreads + threadIdx.x;     // row-major piece (r, p) = (j / kpr, j % kpr)
-        if (j < n) v[i] = base[j];
+        v[i] = base[j < n ? j : n - 1];                       // unconditional loads
     }
     __syncthreads();                                          // waits for this thread's loads, then for everyone's
 #pragma unroll

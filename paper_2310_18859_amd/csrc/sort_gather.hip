@@ -356,8 +356,7 @@ __global__ __launch_bounds__(256) void sort_chunks(const int32_t *__restrict__ i
     for (int base = tid; base < n4; base += 256 * kIdLoads) {
         int4 v[kIdLoads];
 #pragma unroll
-        for (int u = 0; u < kIdLoads; ++u)
-            if (base + u * 256 < n4) v[u] = ids4[base + u * 256];
+        for (int u = 0; u < kIdLoads; ++u) v[u] = ids4[min(base + u * 256, n4 - 1)];   // unconditional loads
 #pragma unroll
         for (int u = 0; u < kIdLoads; ++u)
             if (base + u * 256 < n4) {
@@ -464,26 +463,31 @@ __global__ __launch_bounds__(256) void sort_chunks(const int32_t *__restrict__ i
     }
 }
 
-// Rows of d*2 bytes moved as 16-byte pieces.  The pieces of kGatherRows consecutive output rows are
-// dealt to the 256 threads of a workgroup as one flat range, kGatherUnroll pieces in flight per
-// thread, so that no lane idles whatever the row length (96 pieces at d = 768).
-constexpr int kGatherRows = 16, kGatherUnroll = 4;
+// Rows of d*2 bytes moved as 16-byte pieces.  A workgroup takes kGatherRows consecutive output rows:
+// their source rows go to LDS first, then the rows' pieces are dealt to the 256 threads as one flat
+// range (no lane idles whatever the row length - 96 pieces at d = 768), kGatherUnroll independent
+// loads in flight per thread.
+constexpr int kGatherRows = 8, kGatherUnroll = 4;
 __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ x, const int32_t *__restrict__ perm,
                                                    int T, int vec_per_row, uint4 *__restrict__ x_perm, int k)
 {
+    __shared__ int src_row[kGatherRows];
     const int row0 = blockIdx.x * kGatherRows;
-    const int n = min(kGatherRows, T - row0) * vec_per_row;   // pieces of this workgroup
+    const int rows = min(kGatherRows, T - row0);
+    if ((int)threadIdx.x < rows) {
+        const int t = perm[row0 + threadIdx.x];
+        src_row[threadIdx.x] = k == 1 ? t : t / k;            // row r belongs to token perm[r] / k
+    }
+    __syncthreads();
+    const int n = rows * vec_per_row;                         // pieces of this workgroup
     uint4 *dst = x_perm + (size_t)row0 * vec_per_row;         // its output rows are one contiguous range
     for (int base = threadIdx.x; base < n; base += 256 * kGatherUnroll) {
         uint4 v[kGatherUnroll];
 #pragma unroll
-        for (int u = 0; u < kGatherUnroll; ++u) {
-            const int j = base + u * 256;
-            if (j < n) {
-                const int r = j / vec_per_row, i = j - r * vec_per_row;
-                const int t = k == 1 ? perm[row0 + r] : perm[row0 + r] / k;   // row r belongs to token perm[r] / k
-                v[u] = x[(size_t)t * vec_per_row + i];
-            }
+        for (int u = 0; u < kGatherUnroll; ++u) {             // unconditional loads (past the end: the last piece again)
+            const int j = min(base + u * 256, n - 1);
+            const int r = j / vec_per_row, i = j - r * vec_per_row;
+            v[u] = x[(size_t)src_row[r] * vec_per_row + i];
         }
 #pragma unroll
         for (int u = 0; u < kGatherUnroll; ++u)
