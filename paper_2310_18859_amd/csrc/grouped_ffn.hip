@@ -162,9 +162,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs
     auto locate = [&](int i, Coord *c) {                        // i-th tile of this workgroup; returns its pool slot
         int mt, nt;
         map_tile(wg + i * G, g.m_tiles, g.m_tall, n_tiles_n, g.nw, &mt, &nt);
-        const TileDesc td = g.tiles[mt];                        // uniform address: a scalar load
-        *c = Coord{td.row0, td.rows, nt};
-        return td.slot;
+        const TileDesc td = g.tiles[mt];                        // the same address in every lane
+        // ... and the values declared uniform: descriptors and offsets built from them stay in scalar
+        // registers (a buffer descriptor in vector registers costs a loop around every load)
+        *c = Coord{__builtin_amdgcn_readfirstlane(td.row0), __builtin_amdgcn_readfirstlane(td.rows), nt};
+        return __builtin_amdgcn_readfirstlane(td.slot);
     };
 
     // ---- load side.  Direct load q of a stage fills token rows 8q .. 8q+7 (1 KiB): lane l covers
@@ -298,6 +300,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs
         // rows (read by store_tile()); the previous reads of the buffer are behind this wavefront
         if (FUSE == kGather) fetch_rows_in(nc);
         if (FUSE == kScatter) fetch_rows_out(cc);
+        const int live = (cc.rows + 31) >> 5;                   // 32-row blocks of this tile that hold tokens
 #pragma clang loop unroll(disable)
         for (int kk = 0; kk < nkk; ++kk) {
             if (kk == nkk - 1) {                                // all loads of this tile have been issued
@@ -313,19 +316,23 @@ __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs
                                                                 // everyone is done reading the stage refilled next
                 issue_tokens();
                 const char *st = lds + rd_off;
+                // 32-row blocks of tokens past the tile's end are neither read nor multiplied
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    bf16x8 xf[MI];
+                for (int im = 0; im < MI; ++im)
+                    if (im == 0 || im < live) {
+                        bf16x8 xf[KS];
 #pragma unroll
-                    for (int i = 0; i < MI; ++i) xf[i] = *reinterpret_cast<const bf16x8 *>(st + i * 4096 + x_at[ks]);
+                        for (int ks = 0; ks < KS; ++ks) xf[ks] = *reinterpret_cast<const bf16x8 *>(st + im * 4096 + x_at[ks]);
 #pragma unroll
-                    for (int im = 0; im < MI; ++im)
+                        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                        for (int s = 0; s < NS; ++s)
-                            acc[s][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[b][ks][s], xf[im], acc[s][im], 0, 0, 0);
+                            for (int s = 0; s < NS; ++s)
+                                acc[s][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[b][ks][s], xf[ks], acc[s][im], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                     for (int s = 0; s < NS; ++s) w[b][ks][s] = load_frag(w_rsrc, w_v[s], w_s + ks * 1024);
-                }
                 w_s += 4096;
                 rd_off = rd_off + kStageBytes == kRingBytes ? 0 : rd_off + kStageBytes;
             }
