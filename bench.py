@@ -340,8 +340,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with timing events")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens of the oracle sample (0 = four layers, ~10-15 s)")
-    ap.add_argument("--only", choices=["all", "main"], default="all",
-                    help="main: the one workload's streaming and resident runs, none of the other legs")
+    ap.add_argument("--only", choices=["all", "main", "large_m"], default="all",
+                    help="main: the one workload's streaming and resident runs, none of the other legs; "
+                         "large_m: only the grouped FFN on many-token experts (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sweeps; 0 = as defined)")
@@ -431,10 +432,12 @@ def main():
                 legs["serving"] = {"workload": f"{wl.name}: stream of {a.serve_batches} batches of {a.serve_tokens} tokens, "
                                                f"first {a.serve_batches // 3} untimed", "rows": rows}
 
-    main_w = measure_workload(wl, None, a.steps, a.warmup, a.resident_steps, profile, a.prefetch, a.copy_cus, extra)
+    main_w = None
+    if a.only != "large_m":
+        main_w = measure_workload(wl, None, a.steps, a.warmup, a.resident_steps, profile, a.prefetch, a.copy_cus, extra)
 
     # ---- K-b on many-token experts alone (every expert far above the MFMA/HBM ridge) ---------
-    if full:
+    if full or a.only == "large_m":
         wt = WORKLOADS[0].scaled(d_model=wl.d_model, d_ff=wl.d_ff, T=16384, name=f"{WORKLOADS[0].name}-T16384")
         r3 = MoERunner(wt.L, wt.E, wt.d_model, wt.d_ff, wt.L * wt.E, wt.E, wt.T)
         fill_host_weights(wt, r3.alloc_host_weights())
@@ -453,6 +456,10 @@ def main():
         r3.close()
         if "gemm1" in kern3:
             log(f"[bench] large-M experts alone: gemm1 {kern3['gemm1']['avg_us']:.1f} us, gemm2 {kern3['gemm2']['avg_us']:.1f} us")
+    if a.only == "large_m":
+        print(json.dumps({"kb_large_m": legs["kb_large_m"]}), flush=True)
+        return
+    if full:
         # ---- the hash function's forward pass (predicts the ids / alpha table of a batch)
         legs["hash_fn"] = hash_leg(wl)
         log("[bench] hash function: " + ", ".join(f"{r['sequences']} x {r['seq_len']} tokens {r['ms']:.3f} ms" for r in legs["hash_fn"]["rows"]))
