@@ -967,10 +967,10 @@ int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t 
 {
     if (m_tiles < 0 || m_tall < 0 || m_tall > m_tiles || n_tiles_n < 1 || !token_tile || !weight_tile) return SIDA_EINVAL;
     if ((int64_t)m_tiles * n_tiles_n > INT32_MAX) return SIDA_EINVAL;
-    const int nw = tile_block_width(n_tiles_n);
+    const int gm = tile_group_height(m_tiles, m_tall), nw = tile_block_width(n_tiles_n, gm);
     for (int32_t t = 0; t < m_tiles * n_tiles_n; ++t) {
         int mt, nt;
-        map_tile(t, m_tiles, m_tall, n_tiles_n, nw, &mt, &nt);
+        map_tile(t, m_tiles, m_tall, n_tiles_n, gm, nw, &mt, &nt);
         token_tile[t] = mt;
         weight_tile[t] = nt;
     }

@@ -97,7 +97,7 @@ struct GemmArgs {
     const char *pool;
     size_t expert_bytes, w_off;  // W_in at offset 0 of a slot, W_out behind it
     const TileDesc *tiles;
-    int m_tiles, m_tall, nw, N, K;
+    int m_tiles, m_tall, gm, nw, N, K;      // gm x nw: block of the tile order (tile_order.h)
     uint32_t a_bytes;            // bytes of A
     char *sink;
     const int32_t *perm;         // fused modes: row maps, `map_len` entries
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs
     };
     auto locate = [&](int i, Coord *c) {                        // i-th tile of this workgroup; returns its pool slot
         int mt, nt;
-        map_tile(wg + i * G, g.m_tiles, g.m_tall, n_tiles_n, g.nw, &mt, &nt);
+        map_tile(wg + i * G, g.m_tiles, g.m_tall, n_tiles_n, g.gm, g.nw, &mt, &nt);
         const TileDesc td = g.tiles[mt];                        // the same address in every lane
         // ... and the values declared uniform: descriptors and offsets built from them stay in scalar
         // registers (a buffer descriptor in vector registers costs a loop around every load)
@@ -390,7 +390,8 @@ int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
     }
     GemmArgs g = a;
     const int n_tiles_n = a.N / (kWaves * NS * 32);
-    g.nw = tile_block_width(n_tiles_n);
+    g.gm = tile_group_height(a.m_tiles, a.m_tall);
+    g.nw = tile_block_width(n_tiles_n, g.gm);
     const int total = a.m_tiles * n_tiles_n;
     const int cap = 2 * persistent_grid(st);                 // two workgroups per compute unit
     const int grid = total < cap ? (total + 7) / 8 * 8 : cap;   // multiple of 8 XCDs

@@ -152,7 +152,7 @@ def test_tile_order_visits_every_tile_once():
     """The walk order of a grouped-GEMM launch (the same function the kernels use) is a bijection for
     every mix of many-token and few-token tiles, including the launches whose XCDs alternate the two."""
     rng = np.random.default_rng(5)
-    shapes = [(m, mt, n) for m in (0, 1, 3, 4, 31, 32, 33, 63, 64, 65, 100, 204, 257, 330, 512)
+    shapes = [(m, mt, n) for m in (0, 1, 3, 4, 31, 32, 33, 63, 64, 65, 100, 128, 130, 204, 256, 257, 330, 384, 512)
               for mt in sorted({0, 2 if m >= 2 else 0, m // 3, m // 2, m - m % 4, m}) if mt <= m
               for n in (1, 3, 4, 6, 12, 16, 24)]
     shapes += [(int(rng.integers(1, 700)), 0, int(rng.choice([3, 6, 12, 16, 32]))) for _ in range(40)]
@@ -166,6 +166,12 @@ def test_tile_order_visits_every_tile_once():
     mixed = sm.tile_order(204, 100, 12)
     plain = [(t // 12, t % 12) for t in range(204 * 12)]
     assert mixed != plain and sorted(mixed) == plain
+    # many-token experts alone (8 experts x 16 token tiles): groups of 16 token tiles, so the 64 tiles an
+    # XCD works on at a time share one expert's 16 token tiles and 4 weight-row tiles
+    tall = sm.tile_order(128, 128, 12)
+    for xcd in range(8):
+        first = tall[xcd::8][:64]
+        assert {a // 16 for a, _ in first} == {xcd} and len({b for _, b in first}) == 4
     with pytest.raises(sm.SidaError):
         sm.tile_order(4, 5, 3)
 
