@@ -44,6 +44,21 @@ def check_sort(r, wl, ids, T):
     assert np.array_equal(r.region(T, "inv", torch.int32, (T,)).cpu().numpy(), inv)
 
 
+def reaches_alternating_order(ids, E, tile_m):
+    """Whether a one-launch GEMM over these tokens walks its tiles in the order that alternates blocks
+    of many-token tiles with runs of few-token tiles on every XCD (csrc/tile_order.h: groups of gm
+    token tiles, at least two complete rounds of 8 groups of either kind)."""
+    per = [-(-int(c) // tile_m) for c in np.bincount(ids, minlength=E) if c > 0]
+    m_tiles, m_tall = sum(per), sum(t for t in per if t > 1)
+    gm, slack = 4, max(m_tiles // 16, m_tiles % 32)        # the group height, chosen as tile_group_height does
+    for h in (8, 16):
+        covered, left = (m_tall // (8 * h)) * 8 * h, m_tiles % (8 * h)
+        if covered > 0 and covered * 10 >= (m_tall // 32) * 32 * 9 and left <= slack:
+            gm = h
+    n_many = (m_tall // gm) // 8
+    return min(n_many, (m_tiles // gm) // 8 - n_many) >= 2
+
+
 def check_resident(wl, whole_layers, with_top_k=False):
     say(f"resident launch shape: {wl.name} L={wl.L} E={wl.E} d={wl.d_model} F={wl.d_ff} T={wl.T}, pool of {wl.L * wl.E} slots")
     r = resident_runner(wl)
@@ -51,6 +66,9 @@ def check_resident(wl, whole_layers, with_top_k=False):
     ins = [layer_inputs(wl, l) for l in range(wl.L)]
     plans, _ = run_pass(r, ins)                            # loads every activated expert
     assert all(p.n_waves == 1 for p in plans)
+    # the layers that are checked row by row run the tile order with both kinds of tiles mixed
+    for l in set(whole_layers[False]) | set(whole_layers[True]):
+        assert reaches_alternating_order(ins[l][1], wl.E, 128), f"layer {l}"
     sample = np.arange(0, wl.T, 61)
     outs = {}
     for fused in (False, True):
