@@ -20,10 +20,11 @@
 // return zeros instead of faulting) - and, deliberately, no FLAT-encoded LDS loads: with those in
 // flight the compiler must wait for ALL outstanding loads at every use of a loaded register.
 //
-// Tiling: a workgroup of 4 wavefronts computes BM tokens x (4*NS*32) weight rows; wavefront w owns
-// NS stripes of 32 weight rows and all BM token rows, i.e. NS x BM/32 accumulator blocks of 32x32
-// (fp32).  Two workgroups share a compute unit (8 wavefronts, two per SIMD), so that one's result
-// stores and tile switch overlap the other's MFMAs.  One LDS fragment read feeds NS MFMAs.
+// Tiling: a workgroup of NWV = 4 wavefronts computes BM tokens x (NWV*NS*32) weight rows; wavefront w
+// owns NS stripes of 32 weight rows and all BM token rows, i.e. NS x BM/32 accumulator blocks of
+// 32x32 (fp32).  Two workgroups share a compute unit (8 wavefronts, two per SIMD), so that one's
+// result stores and tile switch overlap the other's MFMAs.  One LDS fragment read feeds NS MFMAs.
+// Launches with few tiles use workgroups of NWV = 2 wavefronts, three per compute unit.
 //
 // LDS token tile layout: row r of a stage is 128 bytes; its 16-byte piece c is stored at piece
 // position c ^ (r & 7).  A direct-to-LDS load writes lane i's 16 bytes at offset 16*i of the
@@ -113,10 +114,9 @@ struct GemmArgs {
 // fetches its own first steps once more, unused, so that the loop has no data-dependent branch).
 // Per step a wavefront executes: one s_waitcnt, one s_barrier, its share of the token loads, and
 // per 16 K values BM/32 LDS fragment reads, NS*BM/32 MFMAs and NS weight-fragment loads.
-template <int BM, int NS, int NB, bool RELU, int FUSE>
-__global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs g)
+template <int BM, int NS, int NB, bool RELU, int FUSE, int NWV>
+__global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_nt(const GemmArgs g)
 {
-    constexpr int NWV = kWaves;
     constexpr int BN = NWV * NS * 32;
     constexpr int TS = NB + 1;                                  // token ring stages
     constexpr int kStageBytes = BM * 128;
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void grouped_gemm_nt(const GemmArgs
     static_assert(QN % NWV == 0 && TL * 8 <= 64, "token loads per wavefront");
     static_assert(kBase + STORES + 4 <= 63, "vmcnt range");
     static_assert(NWV * 64 * 16 <= kGemmSinkBytes / 2, "sink size");
-    static_assert(kRingBytes + kStage + NWV * kSide <= 80 * 1024, "two workgroups per compute unit");
+    static_assert(kRingBytes + kStage + NWV * kSide <= (NWV == kWaves ? 80 : 53) * 1024, "two (three) workgroups per compute unit");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -376,26 +376,26 @@ int persistent_grid(hipStream_t st)
 }
 
 // One GEMM of the pair as one launch: BM token rows per tile, 4*NS*32 weight rows, NB K-steps ahead.
-template <int BM, int NS, int NB, bool RELU, int FUSE>
+template <int BM, int NS, int NB, bool RELU, int FUSE, int NWV = kWaves>
 int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
 {
-    constexpr int kLdsBytes = (NB + 1) * BM * 128 + kWaves * 32 * (NS * 64 + 16) +
-                              kWaves * (FUSE == kPlain ? 0 : (FUSE == kGather ? 256 : 2 * BM * 4));
+    constexpr int kLdsBytes = (NB + 1) * BM * 128 + NWV * 32 * (NS * 64 + 16) +
+                              NWV * (FUSE == kPlain ? 0 : (FUSE == kGather ? 256 : 2 * BM * 4));
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, NS, NB, RELU, FUSE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, NS, NB, RELU, FUSE, NWV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
     GemmArgs g = a;
-    const int n_tiles_n = a.N / (kWaves * NS * 32);
+    const int n_tiles_n = a.N / (NWV * NS * 32);
     g.gm = tile_group_height(a.m_tiles, a.m_tall);
     g.nw = tile_block_width(n_tiles_n, g.gm);
     const int total = a.m_tiles * n_tiles_n;
-    const int cap = 2 * persistent_grid(st);                 // two workgroups per compute unit
+    const int cap = (NWV == kWaves ? 2 : 3) * persistent_grid(st);   // workgroups per compute unit
     const int grid = total < cap ? (total + 7) / 8 * 8 : cap;   // multiple of 8 XCDs
-    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, NS, NB, RELU, FUSE>), dim3(grid), dim3(kWaves * 64), kLdsBytes, st,
+    hipExtLaunchKernelGGL((grouped_gemm_nt<BM, NS, NB, RELU, FUSE, NWV>), dim3(grid), dim3(NWV * 64), kLdsBytes, st,
                           ev ? ev->start : nullptr, ev ? ev->stop : nullptr, 0, g);
     return (int)hipGetLastError();
 }
@@ -417,8 +417,19 @@ int launch_width(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
     const int64_t t_wide = (int64_t)a.m_tiles * (a.N / 256);
     const bool wide = a.N % 256 == 0 && (t_wide + slots - 1) / slots * 8 <= (2 * t_wide + slots - 1) / slots * 5;
     if (wide) return launch_as<BM, 2, 2, RELU, FUSE>(a, st, ev);
-    if constexpr (BM == kGemmTileSmall)
+    if constexpr (BM == kGemmTileSmall) {
+        // 128-wide tiles for at most three quarters of the workgroup slots, and few tokens per tile:
+        // workgroups of two wavefronts (64 weight rows), three per compute unit, put twice as many
+        // weight streams in flight.  (A 128-token batch's second GEMM, 312 tiles: 53 -> 47 us.  With
+        // tiles for 0.8 of the slots and more, or with full token tiles, fetching the token rows twice
+        // as often costs more than the streams gain.)
+        const int64_t rows = a.a_bytes / (2 * (int64_t)a.K);
+        if (4 * (int64_t)a.m_tiles * (a.N / 128) <= 3 * slots && rows <= 32 * (int64_t)a.m_tiles) {
+            if (a.K % 256 == 0) return launch_as<BM, 1, 4, RELU, FUSE, 2>(a, st, ev);
+            return launch_as<BM, 1, 2, RELU, FUSE, 2>(a, st, ev);
+        }
         if (a.K % 256 == 0) return launch_as<BM, 1, 4, RELU, FUSE>(a, st, ev);
+    }
     return launch_as<BM, 1, 2, RELU, FUSE>(a, st, ev);
 }
 
