@@ -114,8 +114,7 @@ typedef struct sida_ws_layout {
     size_t x_perm;      /* bf16  [T, d_model]           x rows in perm order                  */
     size_t h;           /* bf16  [T, d_ff]              relu(x_perm W_in^T), perm order       */
     size_t y_perm;      /* bf16  [T, d_model]           expert outputs, perm order            */
-    size_t tiles;       /* int32 [4 * (T/64 + E + 1)]   token-tile descriptors of the grouped FFN, then 128 ints of
-                         *                                tile tickets (which workgroup takes which tile next)   */
+    size_t tiles;       /* int32 [4 * (T/64 + E + 1)]   token-tile descriptors of the grouped FFN */
     size_t sink;        /* 64 KiB scratch: absorbs the grouped FFN's stores of rows past a tile's end */
     size_t gate_perm;   /* fp32  [T]   gate_perm[r] = alpha[perm[r]]   (fused path only)      */
     size_t total;       /* bytes needed                                                       */

@@ -69,7 +69,7 @@ void layout(const sida_config &cfg, int32_t T, sida_ws_layout *o)
     o->x_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
     o->h = take(2 * (size_t)T * (size_t)cfg.d_ff);
     o->y_perm = take(2 * (size_t)T * (size_t)cfg.d_model);
-    o->tiles = take(sizeof(TileDesc) * max_tiles(cfg, T) + 2 * kTicketInts * sizeof(int32_t));   // + the tile tickets
+    o->tiles = take(sizeof(TileDesc) * max_tiles(cfg, T));
     o->sink = take(kGemmSinkBytes);
     o->gate_perm = take(sizeof(float) * (size_t)T);
     o->total = off;
@@ -324,15 +324,13 @@ int launch_wave_ffn(sida_ctx *c, const LayerSchedule &s, int32_t w, const Ws &ws
         TimedKernel tk(c, SIDA_K_GEMM1);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm1(x ? x : ws.x_perm, ws.h, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(),
-                                                x ? T / c->top_k : T, x ? ws.perm : nullptr, T, c->top_k, s.tbl.tile_m,
-                                                tile_tickets(ws.tiles, ws.max_tiles, 0)));
+                                                x ? T / c->top_k : T, x ? ws.perm : nullptr, T, c->top_k, s.tbl.tile_m));
     }
     {
         TimedKernel tk(c, SIDA_K_GEMM2);
         HIP_TRY(c, (hipError_t)launch_ffn_gemm2(ws.h, y ? y : ws.y_perm, c->pool, c->expert_bytes, tiles, s.m_tiles[w],
                                                 s.m_tall[w], c->cfg.d_model, c->cfg.d_ff, ws.sink, st, tk.get(), T,
-                                                y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr, s.tbl.tile_m,
-                                                tile_tickets(ws.tiles, ws.max_tiles, 0)));
+                                                y ? ws.perm : nullptr, y ? ws.gate_perm : nullptr, s.tbl.tile_m));
     }
     return SIDA_OK;
 }

@@ -105,20 +105,9 @@ struct GemmArgs {
     const int32_t *perm;         // fused modes: row maps, `map_len` entries
     const float *gate_perm;
     int map_len, top_k;
-    int32_t *tickets;            // 8 counters (one per XCD) for this launch, zero when it starts; NULL: fixed deal
-    int32_t *tickets_other;      // the 8 counters of the launch that follows: cleared here
 };
 
-// Persistent workgroups: two per compute unit.  Workgroup b starts with tile b; its further tiles are
-// b+G, b+2G, ... (fixed deal) or, with ticket counters, the next tile of its XCD's sequence that
-// nobody has taken yet: tile G + 8*ticket + b%8, the ticket drawn by one atomic per tile.  Tiles take
-// different times and a launch has only a few per workgroup, so the fixed deal leaves a tail in
-// which a third of the workgroups still work and the others idle.  The next tile has to be known
-// NB K-steps before the current one ends (its first steps are fetched by then), so the ticket is
-// drawn three loop iterations before the end, published through LDS an iteration later (by then
-// the wait at the start of a step has covered the atomic: it is one more vector memory operation
-// of the wavefront) and the tile looked up by all wavefronts after that step's barrier.  K loops
-// shorter than three iterations use the fixed deal.
+// Persistent workgroups: two per compute unit, each walks its tiles t = b, b+G, ...
 //
 // (tile, K-step) is ONE stream of steps: the loads run NB steps ahead of the MFMAs (K/64 is a
 // multiple of NB), also across
@@ -149,23 +138,20 @@ __global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_
     static_assert(QN % NWV == 0 && TL * 8 <= 64, "token loads per wavefront");
     static_assert(kBase + STORES + 4 <= 63, "vmcnt range");
     static_assert(NWV * 64 * 16 <= kGemmSinkBytes / 2, "sink size");
-    static_assert(kRingBytes + kStage + NWV * kSide + 16 <= (NWV == kWaves ? 80 : 53) * 1024, "two (three) workgroups per compute unit");
+    static_assert(kRingBytes + kStage + NWV * kSide <= (NWV == kWaves ? 80 : 53) * 1024, "two (three) workgroups per compute unit");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     char *stg = lds + kRingBytes + wv * (32 * kOutPitch);
     char *side = lds + kRingBytes + kStage + wv * kSide;        // this wavefront's row maps (FUSE != kPlain)
-    int *s_ticket = reinterpret_cast<int *>(lds + kRingBytes + kStage + NWV * kSide);   // the ticket drawn for the next tile
     const int N = g.N, K = g.K;
     const int n_tiles_n = N / BN;
     const int total = g.m_tiles * n_tiles_n;
     const int G = gridDim.x, wg = blockIdx.x;
     if (wg >= total) return;
+    const int n = (total - wg + G - 1) / G;                     // tiles of this workgroup
     const int nkk = K / (64 * NB);
-    const bool draw = g.tickets != nullptr && nkk >= 3;         // tiles after the first by ticket
-    const __amdgpu_buffer_rsrc_t ticket_rsrc = make_rsrc(g.tickets, g.tickets ? kTicketInts * 4u : 0u);
-    if (g.tickets_other && wg == 0 && tid < kTicketInts) g.tickets_other[tid] = 0;
     const int stripe_bytes = 32 * K * 2;
     // results of rows past a tile's end go to a scratch sink (every thread issues all its stores,
     // the waits count them); the two workgroups of a compute unit may share it
@@ -174,9 +160,9 @@ __global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_
     struct Coord {
         int row0, rows, nt;
     };
-    auto locate = [&](int t, Coord *c) {                        // tile t of the launch; returns its pool slot
+    auto locate = [&](int i, Coord *c) {                        // i-th tile of this workgroup; returns its pool slot
         int mt, nt;
-        map_tile(t, g.m_tiles, g.m_tall, n_tiles_n, g.gm, g.nw, &mt, &nt);
+        map_tile(wg + i * G, g.m_tiles, g.m_tall, n_tiles_n, g.gm, g.nw, &mt, &nt);
         // The descriptors were written by an earlier launch: read through the constant address space, a
         // scalar load.  (As a vector load its result is waited for with vmcnt(0), which also waits for
         // every prefetched tile load in flight - once per tile.)  The values are uniform, so descriptors
@@ -295,7 +281,7 @@ __global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_
     };
 
     Coord cc, nc;
-    int slot = locate(wg, &cc);
+    int slot = locate(0, &cc);
     nc = cc;
     if (FUSE == kGather) {                                      // the first tile's row map is needed at once
         fetch_rows_in(cc);
@@ -313,58 +299,27 @@ __global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_
     }
     clear();
 
-    int cur_t = wg;                                             // the tile being multiplied
-    int drawn = 0;                                              // wavefront 0, lane 0: the ticket in flight
-    for (bool more = true; more;) {
-        int next_slot = slot, next_t = -1;                      // used from the last NB steps of this tile on
-        nc = cc;                                                // no next tile: its prefetches repeat this one's first steps
-        if (!draw) {
-            if (cur_t + G < total) {
-                next_t = cur_t + G;
-                next_slot = locate(next_t, &nc);
-            }
-            // row map of the next tile's token rows (read by point()); the previous reads of the
-            // buffer are behind this wavefront
-            if (FUSE == kGather) fetch_rows_in(nc);
-        }
-        // row maps of this tile's result rows (read by store_tile())
+    for (int t = 0; t < n; ++t) {
+        int next_slot = slot;
+        if (t + 1 < n) next_slot = locate(t + 1, &nc);          // used from the last NB steps of this tile on
+        // row maps: of the next tile's token rows (read by point() below), or of this tile's result
+        // rows (read by store_tile()); the previous reads of the buffer are behind this wavefront
+        if (FUSE == kGather) fetch_rows_in(nc);
         if (FUSE == kScatter) fetch_rows_out(cc);
         const int live = (cc.rows + 31) >> 5;                   // 32-row blocks of this tile that hold tokens
 #pragma clang loop unroll(disable)
         for (int kk = 0; kk < nkk; ++kk) {
+            if (kk == nkk - 1) {                                // all loads of this tile have been issued
+                if (FUSE == kGather && nkk == 1) wait_loads<0>();   // else a wait of an earlier step covered the row map
+                point(nc, next_slot);
+            }
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 // result stores of the previous tile may still be outstanding during a tile's first steps
-                if (cur_t != wg && kk == 0) wait_loads<kBase + STORES>();
+                if (t > 0 && kk == 0) wait_loads<kBase + STORES>();
                 else wait_loads<kBase>();
-                if (b == 0 && draw && kk == nkk - 2 && wv == 0) {
-                    if (lane == 0) *s_ticket = drawn;           // the atomic has landed: it was issued NB steps ago
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and the LDS write before the barrier lets the others read
-                }
                 __builtin_amdgcn_s_barrier();                   // everyone's token rows of this step are in LDS, and
                                                                 // everyone is done reading the stage refilled next
-                if (b == 0) {
-                    // One atomic instruction of wavefront 0: lane 0 adds 1 to its XCD's counter; the other
-                    // lanes address past the end of the descriptor, where buffer atomics are dropped.
-                    // (With one address for the whole wavefront, or under `if (lane == 0)`, the compiler
-                    // rewrites the atomic into a wavefront reduction that needs its result at once, i.e.
-                    // waits for every load in flight.)
-                    if (draw && kk == nkk - 3 && wv == 0)
-                        drawn = __builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, ticket_rsrc,
-                                                                               lane == 0 ? (wg & 7) * 4 : kTicketInts * 4 + lane * 4, 0, 0);
-                    if (draw && kk == nkk - 2) {
-                        const int t = G + 8 * __builtin_amdgcn_readfirstlane(*s_ticket) + (wg & 7);
-                        if (t >= G && t < total) {              // (a ticket is never negative; a guard against a counter that was not cleared)
-                            next_t = t;
-                            next_slot = locate(t, &nc);
-                        }
-                        if (FUSE == kGather) fetch_rows_in(nc); // lands NB steps from here, before point() reads it
-                    }
-                    if (kk == nkk - 1) {                        // all loads of this tile have been issued
-                        if (FUSE == kGather && nkk == 1) wait_loads<0>();   // else a wait of an earlier step covered the row map
-                        point(nc, next_slot);
-                    }
-                }
                 issue_tokens();
                 const char *st = lds + rd_off;
                 // 32-row blocks of tokens past the tile's end are neither read nor multiplied
@@ -391,8 +346,6 @@ __global__ __launch_bounds__(NWV * 64, NWV == kWaves ? 2 : 3) void grouped_gemm_
         if (FUSE == kScatter && nkk == 1) wait_loads<0>();      // as above, for this tile's row maps
         store_tile(cc);
         clear();
-        more = next_t >= 0;
-        cur_t = next_t;
         cc = nc;
         slot = next_slot;
     }
@@ -433,7 +386,7 @@ template <int BM, int NS, int NB, bool RELU, int FUSE, int NWV = kWaves>
 int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
 {
     constexpr int kLdsBytes = (NB + 1) * BM * 128 + NWV * 32 * (NS * 64 + 16) +
-                              NWV * (FUSE == kPlain ? 0 : (FUSE == kGather ? 256 : 2 * BM * 4)) + 16;   // + the ticket
+                              NWV * (FUSE == kPlain ? 0 : (FUSE == kGather ? 256 : 2 * BM * 4));
     static bool attr_set = false;                            // per kernel instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&grouped_gemm_nt<BM, NS, NB, RELU, FUSE, NWV>),
@@ -511,7 +464,7 @@ void forget_stream(hipStream_t st)
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
                      const LaunchEvents *ev, int32_t a_rows, const int32_t *perm, int32_t map_len, int32_t top_k,
-                     int32_t tile_m, int32_t *tickets)
+                     int32_t tile_m)
 {
     GemmArgs a{};
     a.A = (const __bf16 *)x_perm;
@@ -529,15 +482,12 @@ int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t exper
     a.perm = perm;
     a.map_len = map_len;
     a.top_k = top_k;
-    a.tickets = tickets;                                     // set 0; GEMM 2 uses set 1
-    a.tickets_other = tickets ? tickets + kTicketInts : nullptr;
     return perm ? launch_shape<true, kGather>(a, tile_m, st, ev) : launch_shape<true, kPlain>(a, tile_m, st, ev);
 }
 
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes, const TileDesc *tiles,
                      int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink, hipStream_t st,
-                     const LaunchEvents *ev, int32_t a_rows, const int32_t *perm, const float *gate_perm, int32_t tile_m,
-                     int32_t *tickets)
+                     const LaunchEvents *ev, int32_t a_rows, const int32_t *perm, const float *gate_perm, int32_t tile_m)
 {
     GemmArgs a{};
     a.A = (const __bf16 *)h;
@@ -556,8 +506,6 @@ int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t exper
     a.gate_perm = gate_perm;
     a.map_len = a_rows;
     a.top_k = 1;                                             // scattering is only defined for one expert per token
-    a.tickets = tickets ? tickets + kTicketInts : nullptr;
-    a.tickets_other = tickets;
     return perm ? launch_shape<false, kScatter>(a, tile_m, st, ev) : launch_shape<false, kPlain>(a, tile_m, st, ev);
 }
 
@@ -570,7 +518,6 @@ __global__ __launch_bounds__(256) void build_tiles(const LayerTable tbl, const i
 {
     __shared__ int s_wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 2 * kTicketInts) tile_tickets(tiles, max_tiles, 0)[tid] = 0;
     int e = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
     if (tid < tbl.n) {
         e = tbl.expert[tid];

@@ -17,25 +17,12 @@ struct LayerTable {
 };
 
 // One token tile of the grouped GEMMs: up to tile_m (64 or 128) consecutive rows of one expert.
-// Behind the max_tiles descriptors of a workspace sit the grouped GEMMs' tile tickets: two sets of
-// kTicketInts ints (one per GEMM of the pair; 8 counters, one per XCD, then spare words).  Whatever
-// writes the descriptors (the sort, launch_build_tiles) clears both sets; each GEMM clears the set
-// of the launch that follows it.
-constexpr int kTicketInts = 64;
-
-__host__ __device__ inline int32_t *tile_tickets(void *tiles, int max_tiles, int set);
-
 struct TileDesc {
     int32_t slot;              // pool slot holding the expert's weights
     int32_t row0;              // first row in x_perm / h / y_perm
     int32_t rows;              // 1..tile_m
     int32_t expert;
 };
-
-__host__ __device__ inline int32_t *tile_tickets(void *tiles, int max_tiles, int set)
-{
-    return reinterpret_cast<int32_t *>(static_cast<TileDesc *>(tiles) + max_tiles) + set * kTicketInts;
-}
 
 // Optional timing of a single-kernel launch: the two events are attached to the kernel's own
 // dispatch, so their elapsed time is the kernel's execution time without the gaps a pair of
@@ -63,17 +50,15 @@ int launch_gather(const void *x, const int32_t *perm, int32_t T, int32_t d, void
 // GEMM 1 then reads row r from x[perm[r] / k] (x_perm = x in token order, k rows per token), GEMM 2 writes
 // bf16(gate_perm[r] * result row r) to y[perm[r]] (y_perm = y in token order).
 // a_rows: rows of the token operand (x_perm / h, or x when gathering), map_len: entries of perm.
-// tickets: tile_tickets(tiles, max_tiles, 0) - both sets, cleared - or NULL for the fixed deal of tiles
-// to workgroups.
 // The experts are read from their pool slots in the slot layout below.
 int launch_ffn_gemm1(const void *x_perm, void *h, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev, int32_t a_rows, const int32_t *perm = nullptr,
-                     int32_t map_len = 0, int32_t k = 1, int32_t tile_m = 128, int32_t *tickets = nullptr);
+                     int32_t map_len = 0, int32_t k = 1, int32_t tile_m = 128);
 int launch_ffn_gemm2(const void *h, void *y_perm, const char *pool, size_t expert_bytes,
                      const TileDesc *tiles, int32_t m_tiles, int32_t m_tall, int32_t d, int32_t F, void *sink,
                      hipStream_t st, const LaunchEvents *ev, int32_t a_rows, const int32_t *perm = nullptr,
-                     const float *gate_perm = nullptr, int32_t tile_m = 128, int32_t *tickets = nullptr);
+                     const float *gate_perm = nullptr, int32_t tile_m = 128);
 
 // Slot layout.  The host block of an expert is W_in [F, d] then W_out [d, F], row-major (the ABI);
 // a pool slot holds the same two matrices, each in MFMA-fragment order: a matrix [R, K] is cut

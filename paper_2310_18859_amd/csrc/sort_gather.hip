@@ -120,7 +120,6 @@ __global__ __launch_bounds__(1024) void sort_scan(int32_t *__restrict__ block_hi
     }
 
     if (tbl.n > 0) {
-        if (tid < 2 * kTicketInts) tile_tickets(tiles, max_tiles, 0)[tid] = 0;
         int ex = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
         if (tid < tbl.n) {
             ex = tbl.expert[tid];
@@ -262,7 +261,6 @@ __global__ __launch_bounds__(NWV * 64) void sort_one(const int32_t *__restrict__
 
     // token tiles of the grouped FFN (as in sort_scan)
     if (tbl.n > 0) {
-        if (tid < 2 * kTicketInts) tile_tickets(tiles, max_tiles, 0)[tid] = 0;
         int ex = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
         if (tid < tbl.n) {
             ex = tbl.expert[tid];
@@ -401,7 +399,6 @@ __global__ __launch_bounds__(256) void sort_chunks(const int32_t *__restrict__ i
 
     // token tiles of the grouped FFN (as in sort_scan), by workgroup 0
     if (blockIdx.x == 0 && tbl.n > 0) {
-        if (tid < 2 * kTicketInts) tile_tickets(tiles, max_tiles, 0)[tid] = 0;
         int ex = 0, slot = 0, off = 0, cnt = 0, n_t = 0;
         if (tid < tbl.n) {
             ex = tbl.expert[tid];
