@@ -23,11 +23,13 @@ def slot_order(block, d, F):
     return np.concatenate(out)
 
 
-def run_and_check(wl, reps=1, T_of=None, check_plan=True, fused=False):
+def run_and_check(wl, reps=1, T_of=None, check_plan=True, fused=False, prefetch=None):
     """Runs all layers `reps` times through sida_run_layers and checks every layer's y, its sort
     outputs and its plan against the oracle."""
     r = make_runner(wl)
     r.ctx.set_fusion(fused)
+    if prefetch:
+        r.ctx.set_prefetch_mode(prefetch)
     st = oracle.PoolState(wl.E, wl.S)
     worst = 0.0
     for rep in range(reps):
@@ -72,6 +74,21 @@ def test_small_shapes(name, L, E, d, F, T, zipf, S, W):
     say(f"layer parity: {name}")
     wl = Workload(100 + len(name), name, L, E, d, F, T, zipf, S, W)
     err = run_and_check(wl, reps=2)
+    say(f"  max rel err {err:.3e}")
+
+
+@pytest.mark.parametrize("prefetch,fused", [("kernel", True), ("copy_engine", False)])
+@pytest.mark.parametrize("name,E,d,F,T,zipf,S,W", [
+    # the largest d_model and d_ff the library takes (K loops of 64 steps, 8 KiB rows; in copy-engine
+    # mode the in-place slot re-ordering at its widest); fewer slots than experts, so slots are reloaded
+    ("widest-rows", 3, 4096, 4096, 150, None, 2, 1),
+    # K not a multiple of 256 (two K-steps of prefetch), N not a multiple of 256 (128-wide tiles only)
+    ("odd-strides", 5, 384, 640, 300, 1.0, 5, 5),
+])
+def test_dimension_limits(name, E, d, F, T, zipf, S, W, prefetch, fused):
+    say(f"layer parity: {name} prefetch={prefetch} fused={fused}")
+    wl = Workload(120 + len(name), name, 1, E, d, F, T, zipf, S, W)
+    err = run_and_check(wl, reps=2, fused=fused, prefetch=prefetch)
     say(f"  max rel err {err:.3e}")
 
 
