@@ -382,9 +382,11 @@ int sida_hash_forward_static(const sida_hash_config *cfg, const float *params_de
 /* Inspection: the order in which a grouped-GEMM launch walks its output tiles.  For a launch over
  * m_tiles token tiles (the first m_tall of them belonging to experts with more than one tile) and
  * n_tiles_n weight-row tiles, fills token_tile[t], weight_tile[t] for t = 0 .. m_tiles*n_tiles_n-1
- * (host arrays); output tile t runs on XCD t % 8.  Host only, no GPU: the device code uses the
- * same function, so tests can check that the order visits every tile exactly once. */
-int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t *token_tile, int32_t *weight_tile);
+ * (host arrays); output tile t runs on XCD t % 8.  long_rows != 0: the order of a GEMM whose weight
+ * rows are longer than the matrix is tall (an expert's second GEMM).  Host only, no GPU: the device
+ * code uses the same function, so tests can check that the order visits every tile exactly once. */
+int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t long_rows, int32_t *token_tile,
+                    int32_t *weight_tile);
 
 /* ---- kernel timing (for the benchmark's roofline figures) ----------------------------------- */
 

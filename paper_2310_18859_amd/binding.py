@@ -84,7 +84,7 @@ def lib():
         "sida_set_debug": (C.c_int, [vp, i32]),
         "sida_debug_mismatch_layer": (C.c_int, [vp]),
         "sida_set_prefetch_mode": (C.c_int, [vp, i32]),
-        "sida_tile_order": (C.c_int, [i32, i32, i32, vp, vp]),
+        "sida_tile_order": (C.c_int, [i32, i32, i32, i32, vp, vp]),
         "sida_hash_param_count": (sz, [C.POINTER(SidaHashConfig)]),
         "sida_hash_workspace_bytes": (sz, [C.POINTER(SidaHashConfig), i32]),
         "sida_hash_forward": (C.c_int, [C.POINTER(SidaHashConfig), vp, vp, i32, i32, vp, vp, vp, sz, vp]),
@@ -132,11 +132,12 @@ def _stream(s) -> int:
     return s.cuda_stream
 
 
-def tile_order(m_tiles: int, m_tall: int, n_tiles_n: int):
-    """[(token tile, weight-row tile)] in the order a grouped-GEMM launch walks its output tiles."""
+def tile_order(m_tiles: int, m_tall: int, n_tiles_n: int, long_rows: bool = False):
+    """[(token tile, weight-row tile)] in the order a grouped-GEMM launch walks its output tiles
+    (long_rows: an expert's second GEMM, whose weight rows are longer than the matrix is tall)."""
     n = m_tiles * n_tiles_n
     a, b = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
-    rc = lib().sida_tile_order(m_tiles, m_tall, n_tiles_n, a, b)
+    rc = lib().sida_tile_order(m_tiles, m_tall, n_tiles_n, int(bool(long_rows)), a, b)
     if rc:
         raise SidaError(rc, "sida_tile_order")
     return list(zip(a[:n], b[:n]))

@@ -963,11 +963,12 @@ int sida_hash_forward_static(const sida_hash_config *h, const float *params_dev,
     return rc == 0 ? SIDA_OK : SIDA_EHIP;
 }
 
-int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t *token_tile, int32_t *weight_tile)
+int sida_tile_order(int32_t m_tiles, int32_t m_tall, int32_t n_tiles_n, int32_t long_rows, int32_t *token_tile,
+                    int32_t *weight_tile)
 {
     if (m_tiles < 0 || m_tall < 0 || m_tall > m_tiles || n_tiles_n < 1 || !token_tile || !weight_tile) return SIDA_EINVAL;
     if ((int64_t)m_tiles * n_tiles_n > INT32_MAX) return SIDA_EINVAL;
-    const int gm = tile_group_height(m_tiles, m_tall), nw = tile_block_width(n_tiles_n, gm);
+    const int gm = tile_group_height(m_tiles, m_tall, long_rows != 0), nw = tile_block_width(n_tiles_n, gm);
     for (int32_t t = 0; t < m_tiles * n_tiles_n; ++t) {
         int mt, nt;
         map_tile(t, m_tiles, m_tall, n_tiles_n, gm, nw, &mt, &nt);

@@ -396,7 +396,7 @@ int launch_as(const GemmArgs &a, hipStream_t st, const LaunchEvents *ev)
     }
     GemmArgs g = a;
     const int n_tiles_n = a.N / (NWV * NS * 32);
-    g.gm = tile_group_height(a.m_tiles, a.m_tall);
+    g.gm = tile_group_height(a.m_tiles, a.m_tall, a.K > a.N);
     g.nw = tile_block_width(n_tiles_n, g.gm);
     const int total = a.m_tiles * n_tiles_n;
     const int cap = (NWV == kWaves ? 2 : 3) * persistent_grid(st);   // workgroups per compute unit

@@ -84,7 +84,12 @@ SIDA_HD void map_tile(int t, int m_tiles, int m_tall, int n_tiles_n, int gm, int
 // Token tiles per group.  Taller groups re-read a many-token expert's weights less often, but only
 // complete rounds of 8 groups get the block order: the tallest of 16, 8, 4 that still covers (nearly)
 // as many many-token tiles as groups of 4 do and leaves no more tiles to the plain order at the end.
-SIDA_HD int tile_group_height(int m_tiles, int m_tall)
+// long_rows (weight rows longer than the matrix is tall, K > N: the second GEMM of an expert): at
+// least 8 once there is a complete round of such groups - a pass over 8 token tiles' rows of K
+// values keeps a block's workgroups together for long, the expert's weights are fetched half as
+// often (measured on the Switch shapes: 8 % fewer bytes missing L2, up to 7 % less time; for the
+// first GEMM, K < N, the coarser alternation of the two kinds of tiles costs more than that).
+SIDA_HD int tile_group_height(int m_tiles, int m_tall, bool long_rows)
 {
     const int covered4 = (m_tall / 32) * 32, left4 = m_tiles - (m_tiles / 32) * 32;
     const int slack = m_tiles / 16 > left4 ? m_tiles / 16 : left4;
@@ -93,6 +98,7 @@ SIDA_HD int tile_group_height(int m_tiles, int m_tall)
         const int covered = (m_tall / (8 * h)) * 8 * h, left = m_tiles - (m_tiles / (8 * h)) * 8 * h;
         if (covered > 0 && covered * 10 >= covered4 * 9 && left <= slack) gm = h;
     }
+    if (long_rows && gm < 8 && m_tall >= 64) gm = 8;
     return gm;
 }
 

@@ -159,9 +159,10 @@ def test_tile_order_visits_every_tile_once():
     for m, mt, n in shapes:
         if mt == 0 and rng.random() < 0.5 and m > 8:
             mt = int(rng.integers(0, m + 1))
-        order = sm.tile_order(m, mt, n)
-        assert len(order) == m * n
-        assert sorted(order) == [(a, b) for a in range(m) for b in range(n)], (m, mt, n)
+        for long_rows in (False, True):
+            order = sm.tile_order(m, mt, n, long_rows)
+            assert len(order) == m * n
+            assert sorted(order) == [(a, b) for a in range(m) for b in range(n)], (m, mt, n, long_rows)
     # cases where the mixing is active: at least two rounds (64 token tiles) of either kind
     mixed = sm.tile_order(204, 100, 12)
     plain = [(t // 12, t % 12) for t in range(204 * 12)]
@@ -172,6 +173,11 @@ def test_tile_order_visits_every_tile_once():
     for xcd in range(8):
         first = tall[xcd::8][:64]
         assert {a // 16 for a, _ in first} == {xcd} and len({b for _, b in first}) == 4
+    # an expert's second GEMM at the Switch-base-128 shape: groups of 8 token tiles, so an XCD starts with
+    # one many-token expert's 8 token tiles against all 6 weight-row tiles
+    second = sm.tile_order(204, 100, 6, True)
+    assert second != sm.tile_order(204, 100, 6, False) and sorted(second) == [(t // 6, t % 6) for t in range(204 * 6)]
+    assert sorted(second[0::8][:48]) == [(a, b) for a in range(8) for b in range(6)]
     with pytest.raises(sm.SidaError):
         sm.tile_order(4, 5, 3)
 
