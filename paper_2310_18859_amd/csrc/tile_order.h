@@ -85,10 +85,12 @@ SIDA_HD void map_tile(int t, int m_tiles, int m_tall, int n_tiles_n, int gm, int
 // complete rounds of 8 groups get the block order: the tallest of 16, 8, 4 that still covers (nearly)
 // as many many-token tiles as groups of 4 do and leaves no more tiles to the plain order at the end.
 // long_rows (weight rows longer than the matrix is tall, K > N: the second GEMM of an expert): at
-// least 8 once there is a complete round of such groups - a pass over 8 token tiles' rows of K
-// values keeps a block's workgroups together for long, the expert's weights are fetched half as
-// often (measured on the Switch shapes: 8 % fewer bytes missing L2, up to 7 % less time; for the
-// first GEMM, K < N, the coarser alternation of the two kinds of tiles costs more than that).
+// least 8 when both kinds of tiles still fill two rounds of such groups, i.e. when the XCDs keep
+// alternating between them - a pass over 8 token tiles' rows of K values keeps a block's workgroups
+// together for long, the expert's weights are fetched half as often (measured at the Switch-large
+// shape: 388 -> 373 us; at Switch-base-128, where groups of 8 leave one round of many-token tiles
+// and the alternation stops, groups of 4 are faster, 159 against 165 us; for the first GEMM, K < N,
+// the coarser alternation costs more than the saved fetches at either shape).
 SIDA_HD int tile_group_height(int m_tiles, int m_tall, bool long_rows)
 {
     const int covered4 = (m_tall / 32) * 32, left4 = m_tiles - (m_tiles / 32) * 32;
@@ -98,7 +100,10 @@ SIDA_HD int tile_group_height(int m_tiles, int m_tall, bool long_rows)
         const int covered = (m_tall / (8 * h)) * 8 * h, left = m_tiles - (m_tiles / (8 * h)) * 8 * h;
         if (covered > 0 && covered * 10 >= covered4 * 9 && left <= slack) gm = h;
     }
-    if (long_rows && gm < 8 && m_tall >= 64) gm = 8;
+    if (long_rows && gm < 8) {
+        const int many8 = (m_tall / 8) / 8, few8 = (m_tiles / 8) / 8 - many8;
+        if (many8 >= 2 && few8 >= 2) gm = 8;
+    }
     return gm;
 }
 

@@ -173,11 +173,12 @@ def test_tile_order_visits_every_tile_once():
     for xcd in range(8):
         first = tall[xcd::8][:64]
         assert {a // 16 for a, _ in first} == {xcd} and len({b for _, b in first}) == 4
-    # an expert's second GEMM at the Switch-base-128 shape: groups of 8 token tiles, so an XCD starts with
-    # one many-token expert's 8 token tiles against all 6 weight-row tiles
-    second = sm.tile_order(204, 100, 6, True)
-    assert second != sm.tile_order(204, 100, 6, False) and sorted(second) == [(t // 6, t % 6) for t in range(204 * 6)]
-    assert sorted(second[0::8][:48]) == [(a, b) for a in range(8) for b in range(6)]
+    # an expert's second GEMM with two rounds of either kind of tile in groups of 8 (the Switch-large
+    # shape): an XCD starts with one many-token expert's 8 token tiles against all weight-row tiles
+    second = sm.tile_order(328, 234, 4, True)
+    assert second != sm.tile_order(328, 234, 4, False) and sorted(second) == [(t // 4, t % 4) for t in range(328 * 4)]
+    assert sorted(second[0::8][:32]) == [(a, b) for a in range(8) for b in range(4)]
+    assert sm.tile_order(204, 100, 6, True) == sm.tile_order(204, 100, 6, False)     # one round only: groups of 4
     with pytest.raises(sm.SidaError):
         sm.tile_order(4, 5, 3)
 
