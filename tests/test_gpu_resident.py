@@ -123,3 +123,46 @@ def test_resident_switch_base_256():
 
 def test_resident_switch_large_128():
     check_resident(WORKLOADS[4].scaled(L=2), whole_layers={False: (1,), True: (0,)})
+
+
+def test_rows_do_not_depend_on_their_neighbours():
+    """A property that holds at any size and needs no oracle: a token's output row is a function of its own
+    x row, expert id and gate only (Eq. 1), and the kernels sum over K in the same order wherever the
+    row lands in a tile - so shuffling the tokens of a full-size layer shuffles y bit for bit.  Covers
+    every row of the layers that the oracle only samples."""
+    wl = WORKLOADS[2].scaled(L=2)
+    say(f"token permutation at full size: {wl.name} T={wl.T}")
+    r = resident_runner(wl)
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    run_pass(r, ins)                                       # loads every activated expert
+    rng = np.random.default_rng(11)
+    for fused in (True, False):
+        r.ctx.set_fusion(fused)
+        _, dev = run_pass(r, ins)
+        y = [d[3].view(torch.uint16).cpu().numpy() for d in dev]
+        shuffle = [rng.permutation(wl.T) for _ in range(wl.L)]
+        ins_s = [(x[p], ids[p], a[p]) for (x, ids, a), p in zip(ins, shuffle)]
+        _, dev_s = run_pass(r, ins_s)
+        for l in range(wl.L):
+            y_s = dev_s[l][3].view(torch.uint16).cpu().numpy()
+            assert np.array_equal(y_s, y[l][shuffle[l]]), f"fused={fused} layer {l}"
+    r.close()
+
+
+def test_doubling_the_gates_doubles_y_exactly():
+    """Another property without an oracle: y = bf16(alpha * bf16(sum)) (Eq. 1), so with every gate
+    doubled - an exact operation in fp32 and in bf16 - every output doubles bit for bit, at full size,
+    on the fused path and with the separate combine pass."""
+    wl = WORKLOADS[3].scaled(L=1)
+    say(f"gate scaling at full size: {wl.name} T={wl.T}")
+    r = resident_runner(wl)
+    ins = [layer_inputs(wl, 0)]
+    run_pass(r, ins)
+    for fused in (True, False):
+        r.ctx.set_fusion(fused)
+        _, dev = run_pass(r, ins)
+        y = bf16_tensor_to_f32(dev[0][3])
+        x, ids, alpha = ins[0]
+        _, dev2 = run_pass(r, [(x, ids, (2.0 * alpha).astype(np.float32))])
+        assert np.array_equal(bf16_tensor_to_f32(dev2[0][3]), 2.0 * y), f"fused={fused}"
+    r.close()
