@@ -166,3 +166,33 @@ def test_doubling_the_gates_doubles_y_exactly():
         _, dev2 = run_pass(r, [(x, ids, (2.0 * alpha).astype(np.float32))])
         assert np.array_equal(bf16_tensor_to_f32(dev2[0][3]), 2.0 * y), f"fused={fused}"
     r.close()
+
+
+@pytest.mark.parametrize("mode", ["kernel", "copy_engine"])
+def test_streaming_through_a_small_pool_equals_resident_bit_for_bit(mode):
+    """The benchmark's streaming configuration (32 slots, waves of 16 experts, 64-row tiles, every
+    expert copied in while the previous wave computes) against the resident one (768 slots, one
+    launch per layer, 128-row tiles): the same sums in the same K order, so every row of every
+    layer must agree bit for bit - a slot read before its copy landed, or overwritten before its
+    last reader finished, would show.  Both prefetch modes."""
+    from gpu_util import make_runner
+    wl = WORKLOADS[2]
+    say(f"streaming == resident at full size: {wl.name}, prefetch by {mode}")
+    ins = [layer_inputs(wl, l) for l in range(wl.L)]
+    rs = make_runner(wl)                                   # the workload's own pool: S = 32, W = 16
+    rs.ctx.set_prefetch_mode(mode)
+    run_pass(rs, ins)
+    plans, dev = run_pass(rs, ins)                         # steady state: every expert is a miss again
+    assert sum(p.n_miss for p in plans) == sum(p.n_active for p in plans) and all(p.n_waves > 1 for p in plans)
+    y_stream = [d[3].view(torch.uint16).cpu().numpy() for d in dev]
+    hw = rs.host_weights
+    rr = MoERunner(wl.L, wl.E, wl.d_model, wl.d_ff, wl.L * wl.E, wl.E, wl.T)
+    rr.host_weights = hw
+    rr.ctx.bind_host_weights([hw.data_ptr() + i * rr.expert_bytes for i in range(wl.L * wl.E)], keep=hw)
+    run_pass(rr, ins)
+    plans, dev = run_pass(rr, ins)
+    assert sum(p.n_miss for p in plans) == 0
+    for l in range(wl.L):
+        assert np.array_equal(dev[l][3].view(torch.uint16).cpu().numpy(), y_stream[l]), f"layer {l}"
+    rs.close()
+    rr.close()
