@@ -168,16 +168,16 @@ def test_doubling_the_gates_doubles_y_exactly():
     r.close()
 
 
-@pytest.mark.parametrize("mode", ["kernel", "copy_engine"])
-def test_streaming_through_a_small_pool_equals_resident_bit_for_bit(mode):
-    """The benchmark's streaming configuration (32 slots, waves of 16 experts, 64-row tiles, every
-    expert copied in while the previous wave computes) against the resident one (768 slots, one
-    launch per layer, 128-row tiles): the same sums in the same K order, so every row of every
+@pytest.mark.parametrize("index,layers,mode", [(2, 6, "kernel"), (2, 6, "copy_engine"), (3, 2, "kernel"), (4, 2, "kernel")])
+def test_streaming_through_a_small_pool_equals_resident_bit_for_bit(index, layers, mode):
+    """A workload's streaming configuration (for the benchmark's: 32 slots, waves of 16 experts, 64-row
+    tiles, every expert copied in while the previous wave computes) against the resident one (a slot
+    per expert, one launch per layer, 128-row tiles): the same sums in the same K order, so every row of every
     layer must agree bit for bit - a slot read before its copy landed, or overwritten before its
     last reader finished, would show.  Both prefetch modes."""
     from gpu_util import make_runner
-    wl = WORKLOADS[2]
-    say(f"streaming == resident at full size: {wl.name}, prefetch by {mode}")
+    wl = WORKLOADS[index] if layers == WORKLOADS[index].L else WORKLOADS[index].scaled(L=layers)
+    say(f"streaming == resident at full size: {wl.name} ({layers} layers), prefetch by {mode}")
     ins = [layer_inputs(wl, l) for l in range(wl.L)]
     rs = make_runner(wl)                                   # the workload's own pool: S = 32, W = 16
     rs.ctx.set_prefetch_mode(mode)
